@@ -1,0 +1,220 @@
+"""Pins for the token dispatcher oracle (Algorithm 1, Sec. 4.2)."""
+import itertools
+import os
+from fractions import Fraction
+
+import numpy as np
+import pytest
+
+from oracle import moe_layer as om
+from oracle import planner as op
+from workloads import CONFIGS, step_inputs
+
+from dispatch_checks import check_row_maps, check_schedule_invariants
+
+
+def _parse_case(line):
+    f = dict(tok.split("=") for tok in line.split())
+    R = [int(v) for v in f["R"].split(",")]
+    Tej = [int(v) for v in f["Tej"].split(",")]
+    cap = [int(v) for v in f["cap"].split(",")]
+    recv = [int(v) for v in f["recv"].split(",")]
+    D = {}
+    for row in f["D"].split(";"):
+        i, vals = row.split(":")
+        D[int(i)] = [int(v) for v in vals.split(",")]
+    return R, Tej, cap, recv, D
+
+
+def test_handworked_cases(golden_dir):
+    with open(os.path.join(golden_dir, "schedule_handworked.txt")) as fh:
+        lines = [l.strip() for l in fh if l.strip() and not l.startswith("#")]
+    assert len(lines) >= 2
+    for line in lines:
+        R, Tej, cap, recv, D = _parse_case(line)
+        sch = om.schedule(np.array([Tej]), np.array([R]))
+        assert list(sch["cap"][0]) == cap
+        assert list(sch["recv"][0]) == recv
+        for i, row in D.items():
+            assert list(sch["D"][0, i]) == row
+
+
+def _random_case(rng, E, N, c, tmax):
+    slot_expert = rng.integers(0, E, size=N * c)
+    slot_expert[:E] = np.arange(E) if N * c >= E else slot_expert[:E]
+    rng.shuffle(slot_expert)
+    R = om.replicas_per_rank(slot_expert, E, N, c)
+    Tej = rng.integers(0, tmax, size=(E, N))
+    Tej[rng.random((E, N)) < 0.2] = 0
+    return slot_expert, R, Tej
+
+
+def test_real_valued_algorithm_conserves_and_balances():
+    """The paper's real-valued rule, with the spreading denominator read as the residual
+    capacity of the ranks other than the sender: every token is sent exactly once and
+    every rank receives exactly p_e * R[e,j] (each replica the same share, Sec. 4.2)."""
+    rng = np.random.default_rng(0)
+    for _ in range(50):
+        E, N, c = int(rng.integers(1, 5)), int(rng.integers(1, 6)), int(rng.integers(1, 4))
+        if N * c < E:
+            continue
+        _, R, Tej = _random_case(rng, E, N, c, 30)
+        D = om.schedule_real(Tej, R)
+        for e in range(E):
+            t_e, r_e = int(Tej[e].sum()), int(R[e].sum())
+            for i in range(N):
+                assert sum(D[e][i]) == int(Tej[e, i])
+            for j in range(N):
+                if t_e:
+                    assert sum(D[e][i][j] for i in range(N)) == Fraction(t_e, r_e) * int(R[e, j])
+
+
+def test_printed_denominator_would_lose_tokens():
+    """Why the printed sum over k != j is not taken literally: with it a sender's shares
+    do not add up to its overflow."""
+    R = [1, 1, 1]
+    Tej = [9, 0, 0]                       # cap 3 each; rank 0 overflows 6, residual 0,3,3
+    res = [Fraction(0), Fraction(3), Fraction(3)]
+    overflow = 6
+    printed = [overflow * res[j] / sum(res[k] for k in range(3) if k != j) for j in (1, 2)]
+    assert sum(printed) != overflow
+    D = om.schedule_real(np.array([Tej]), np.array([R]))
+    assert [D[0][0][j] for j in range(3)] == [3, 3, 3]
+
+
+def test_integer_schedule_equals_real_when_real_is_integral():
+    """Where the paper's real-valued formula already yields whole tokens the integer
+    reading must reproduce it exactly."""
+    rng = np.random.default_rng(1)
+    hits = 0
+    for _ in range(4000):
+        N = int(rng.integers(2, 5))
+        c = int(rng.integers(1, 4))
+        _, R, Tej = _random_case(rng, 1, N, c, 13)
+        Dr = om.schedule_real(Tej, R)
+        if all(v.denominator == 1 for row in Dr[0] for v in row):
+            Dint = np.array([[int(v) for v in row] for row in Dr[0]])
+            if (Dint - np.diag(np.diag(Dint))).sum() == 0:
+                continue                  # keep only cases that really spread overflow
+            Di = om.schedule(Tej, R)["D"][0]
+            assert Dint.tolist() == Di.tolist()
+            hits += 1
+    assert hits > 50
+
+
+def test_integer_schedule_close_to_real():
+    """Local shares differ from the real-valued ones by less than one token; spread
+    shares by less than N + 1 (residual capacities each move by < 1, their total by < N)."""
+    rng = np.random.default_rng(2)
+    for _ in range(300):
+        E, N, c = 2, int(rng.integers(2, 6)), int(rng.integers(1, 4))
+        _, R, Tej = _random_case(rng, E, N, c, 200)
+        Dr = om.schedule_real(Tej, R)
+        sch = om.schedule(Tej, R)
+        check_schedule_invariants(Tej, R, sch)
+        for e in range(E):
+            for i in range(N):
+                for j in range(N):
+                    bound = 1 if i == j else N + 1
+                    assert abs(Dr[e][i][j] - int(sch["D"][e, i, j])) < bound
+
+
+def test_traditional_ep_is_stable_sort():
+    """One replica per expert (traditional expert parallelism, Sec. 4.2): every pair of an
+    expert goes to its single slot, so the whole dispatch is a stable sort of the pairs
+    by the slot of their expert."""
+    rng = np.random.default_rng(3)
+    E, N, c, T, k = 12, 4, 3, 97, 3
+    slot_expert = rng.permutation(E)
+    logits = rng.standard_normal((T, E)).astype(np.float32)
+    ids, _ = om.route(logits, k)
+    off = np.array([0, 20, 50, 51, 97])
+    out = om.plan_dispatch(ids, off, slot_expert, E, N, c)
+    slot_of = np.empty(E, dtype=np.int64)
+    slot_of[slot_expert] = np.arange(E)
+    key = slot_of[ids.reshape(-1)]
+    assert np.array_equal(out["row_to_pair"], np.argsort(key, kind="stable"))
+    assert np.array_equal(out["slot_counts"], np.bincount(key, minlength=E))
+
+
+def test_single_rank_all_local():
+    rng = np.random.default_rng(4)
+    E, N, c, T, k = 4, 1, 6, 50, 2
+    slot_expert = np.array([0, 1, 2, 3, 3, 3])
+    ids, _ = om.route(rng.standard_normal((T, E)).astype(np.float32), k)
+    out = om.plan_dispatch(ids, np.array([0, T]), slot_expert, E, N, c)
+    assert np.array_equal(out["D"][:, 0, 0], out["Tej"][:, 0])
+    check_row_maps(ids, np.array([0, T]), slot_expert, E, N, c, out["D"], out)
+    n3 = int(out["Tej"][3, 0])
+    assert list(out["slot_counts"][3:]) == [n3 // 3, (2 * n3) // 3 - n3 // 3, n3 - (2 * n3) // 3]
+
+
+def test_uniform_full_replication_is_diagonal():
+    """Every rank holds every expert once and routing is identical on every rank: each
+    rank is exactly at capacity and nothing moves."""
+    E, N, c, k = 3, 4, 3, 1
+    per_rank = np.array([0, 0, 1, 2, 2, 2, 1])
+    ids = np.tile(per_rank, N).reshape(-1, 1).astype(np.int32)
+    T = ids.shape[0]
+    off = np.arange(N + 1) * len(per_rank)
+    slot_expert = np.tile(np.arange(E), N)
+    out = om.plan_dispatch(ids, off, slot_expert, E, N, c)
+    for e in range(E):
+        assert np.array_equal(out["D"][e], np.diag(out["Tej"][e]))
+    row_rank = (np.searchsorted(out["slot_offsets"], out["pair_to_row"], side="right") - 1) // c
+    assert np.array_equal(row_rank, np.arange(T) // len(per_rank))
+
+
+def test_exhaustive_tiny_row_maps():
+    """Every routing of a few tokens over every small plan: invariants of the counts and
+    uniqueness properties of the row maps."""
+    n_cases = 0
+    for E, N, c, T in [(2, 2, 2, 4), (3, 3, 1, 4), (2, 3, 2, 5), (3, 2, 2, 4)]:
+        plans = [p for p in itertools.product(range(E), repeat=N * c) if len(set(p)) == E]
+        plans = plans[::max(1, len(plans) // 12)]
+        offs = [np.array([(i * T) // N for i in range(N + 1)]), np.array([0] * N + [T]),
+                np.array([0, 1] + [T] * (N - 1))]
+        for routing in itertools.product(range(E), repeat=T):
+            ids = np.array(routing, dtype=np.int32).reshape(T, 1)
+            for plan in plans:
+                for off in offs:
+                    out = om.plan_dispatch(ids, off, np.array(plan), E, N, c)
+                    check_schedule_invariants(out["Tej"], out["R"], out)
+                    check_row_maps(ids, off, np.array(plan), E, N, c, out["D"], out)
+                    n_cases += 1
+    assert n_cases > 5000
+
+
+def test_topk_pairs_and_c1_plan():
+    cfg = CONFIGS["c1_tiny"]
+    inp = step_inputs(cfg)
+    ids, _ = om.route(inp["logits"], cfg.k)
+    plan = np.array(op.place_spread(cfg.replica_counts, cfg.N, cfg.c))
+    out = om.plan_dispatch(ids, inp["rank_tok_off"], plan, cfg.E, cfg.N, cfg.c)
+    check_schedule_invariants(out["Tej"], out["R"], out)
+    check_row_maps(ids, inp["rank_tok_off"], plan, cfg.E, cfg.N, cfg.c, out["D"], out)
+    assert out["slot_counts"].sum() == cfg.T * cfg.k
+    # per expert, its slots' rows add up to its load
+    for e in range(cfg.E):
+        assert out["slot_counts"][plan == e].sum() == out["Tej"][e].sum()
+    # a pair stays on its own rank whenever that rank is within capacity for the expert
+    row_rank = (np.searchsorted(out["slot_offsets"], out["pair_to_row"], side="right") - 1) // cfg.c
+    src = om.source_rank(inp["rank_tok_off"], cfg.T)
+    flat = ids.reshape(-1)
+    for p in range(cfg.T * cfg.k):
+        e, i = flat[p], src[p // cfg.k]
+        if out["O"][e, i] == 0:
+            assert row_rank[p] == i
+
+
+def test_schedule_rejects_uncovered_expert():
+    with pytest.raises(ValueError):
+        om.schedule(np.array([[3, 0]]), np.array([[0, 0]]))
+
+
+def test_permute_is_row_gather():
+    x = np.arange(12, dtype=np.float32).reshape(4, 3)
+    r2p = np.array([7, 0, 3, 2, 1, 6, 5, 4])
+    xp = om.permute(x, r2p, 2)
+    for row, p in enumerate(r2p):
+        assert np.array_equal(xp[row], x[p // 2])

@@ -1,0 +1,269 @@
+"""Pins for the planning oracle: Eq. 1, MRO placement (Theorem 1), spread placement,
+recovery probability, replan (Sec. 4.1, 4.3, 6.3)."""
+import itertools
+import os
+from fractions import Fraction
+from math import comb
+
+import numpy as np
+import pytest
+
+from oracle import planner as op
+
+
+def _ints(s):
+    return [int(v) for v in s.split(",")]
+
+
+def test_allocation_handworked(golden_dir):
+    with open(os.path.join(golden_dir, "allocation_handworked.txt")) as fh:
+        lines = [l.strip() for l in fh if l.strip() and not l.startswith("#")]
+    assert len(lines) >= 3
+    for line in lines:
+        f = dict(tok.split("=") for tok in line.split())
+        slots = int(f["slots"])
+        assert op.allocate_replicas(_ints(f["t"]), slots, 1, int(f["f"])) == _ints(f["r"])
+
+
+def test_allocation_invariants_random():
+    """Eq. 1's stated guarantees: all slots used, r_e >= f, non-decreasing in load order,
+    and roughly proportional to load."""
+    rng = np.random.default_rng(0)
+    for _ in range(500):
+        E = int(rng.integers(1, 20))
+        N = int(rng.integers(1, 12))
+        c = int(rng.integers(1, 9))
+        f = int(rng.integers(1, 4))
+        if N * c < E:
+            with pytest.raises(op.Infeasible):
+                op.allocate_replicas([1] * E, N, c, f)
+            continue
+        t = rng.integers(0, 1000, size=E)
+        if rng.random() < 0.2:
+            t[rng.random(E) < 0.5] = 0
+        r = op.allocate_replicas(t, N, c, f)
+        f_eff = min(f, (N * c) // E)
+        assert sum(r) == N * c and min(r) >= f_eff
+        order = op.load_order(t)
+        assert all(r[order[a]] <= r[order[a + 1]] for a in range(E - 1))
+        if t.sum() > 0 and f_eff == 1:
+            # an expert never gets more than its proportional share plus what flooring
+            # and the minimum left over from the less loaded ones
+            for e in range(E):
+                assert r[e] <= max(1, t[e] / t.sum() * N * c + E)
+
+
+def test_allocation_all_zero_load_is_even():
+    assert sorted(op.allocate_replicas([0, 0, 0], 2, 4, 1)) == [2, 3, 3]
+
+
+def test_spread_c1_fixture():
+    plan = op.place_spread([3, 3, 2, 2, 2, 2, 1, 1], 4, 4)
+    assert [plan[j * 4:(j + 1) * 4] for j in range(4)] == \
+        [[0, 1, 3, 5], [0, 1, 3, 5], [0, 2, 4, 6], [1, 2, 4, 7]]
+
+
+def _paper_values(golden_dir):
+    vals = {}
+    with open(os.path.join(golden_dir, "paper_recovery_values.txt")) as fh:
+        for line in fh:
+            if line.strip() and not line.startswith("#"):
+                name, frac = line.split()[:2]
+                vals[name] = Fraction(frac)
+    return vals
+
+
+def test_paper_printed_probabilities(golden_dir):
+    vals = _paper_values(golden_dir)
+    # Fig. 3 text: 4 experts, 5 nodes, 4 slots per node, 3 failures (2 alive).  The best
+    # plan printed reaches 7/10 = 1 - C(3,2)/C(5,2), i.e. the least loaded expert has 2 replicas.
+    for r in ([2, 4, 6, 8], [2, 2, 8, 8], [2, 6, 6, 6]):
+        plan = op.place_mro(r, r, 5, 4)
+        assert op.recovery_probability(plan, 4, 5, 4, 2) == vals["fig3_planB_recovery"]
+        assert op.recovery_probability(plan, 4, 5, 4, 2) >= vals["fig3_planA_recovery"]
+    # Fig. 4 text: two expert groups on 5 nodes, 3 failures: optimal failure probability 4/10,
+    # reached by node groups of 2 and 3 nodes (both must keep one node alive: 2*3 of 10 pairs).
+    r = [2, 2, 3, 3]
+    plan = op.place_mro(r, r, 5, 2)
+    assert 1 - op.recovery_probability(plan, 4, 5, 2, 2) == vals["fig4_optimal_failure"]
+    # a plan whose overlap is not maximised does worse, e.g. the printed case II level
+    worse = [0, 1, 0, 2, 1, 3, 2, 3, 2, 3]
+    assert sorted(np.bincount(worse).tolist()) == sorted(r)
+    assert 1 - op.recovery_probability(worse, 4, 5, 2, 2) >= vals["fig4_case2_failure"] - Fraction(1, 10)
+
+
+def _group_sizes(r_sorted, N, c):
+    E = len(r_sorted)
+    G = -(-E // c)
+    sizes, used = [], 0
+    for g in range(G):
+        first = r_sorted[g * c]
+        size = first if g < G - 1 else min(N - used, first)
+        sizes.append(size)
+        used += size
+    return sizes
+
+
+def _closed_form(r_sorted, N, c, n_alive):
+    """Theorem 1's value: the probability that n_alive uniformly drawn nodes hit every
+    node-group segment; inclusion-exclusion over the groups that are missed."""
+    sizes = _group_sizes(r_sorted, N, c)
+    total = 0
+    for miss in itertools.product([0, 1], repeat=len(sizes)):
+        lost = sum(s for s, m in zip(sizes, miss) if m)
+        total += (-1) ** sum(miss) * comb(N - lost, n_alive)
+    return Fraction(total, comb(N, n_alive))
+
+
+def test_mro_matches_closed_form_and_structure():
+    rng = np.random.default_rng(1)
+    checked = 0
+    for _ in range(200):
+        E = int(rng.integers(1, 9))
+        N = int(rng.integers(2, 8))
+        c = int(rng.integers(1, 6))
+        if N * c < E:
+            continue
+        t = rng.integers(1, 200, size=E)
+        r = op.allocate_replicas(t, N, c, int(rng.integers(1, 3)))
+        plan = op.place_mro(r, t, N, c)
+        assert np.array_equal(np.bincount(plan, minlength=E), r)
+        order = op.placement_order(r, t)
+        r_sorted = [r[e] for e in order]
+        sizes = _group_sizes(r_sorted, N, c)
+        # structural definition: node j of group g holds every expert of group g
+        node = 0
+        for g, size in enumerate(sizes):
+            members = {order[q] for q in range(g * c, min((g + 1) * c, E))}
+            for j in range(node, node + size):
+                assert members <= set(plan[j * c:(j + 1) * c])
+            node += size
+        if E <= c:
+            assert sizes == [min(r_sorted[0], N)] or sizes == [r_sorted[0]]
+            for e in range(E):          # nested node sets: expert on the first min(r,N) nodes
+                for j in range(min(r[e], N)):
+                    assert e in plan[j * c:(j + 1) * c]
+        for n_alive in range(1, N + 1):
+            p = op.recovery_probability(plan, E, N, c, n_alive)
+            if E <= c:
+                r1 = min(r_sorted[0], N)
+                assert p == 1 - Fraction(comb(N - r1, n_alive), comb(N, n_alive))
+            else:
+                # the guaranteed groups give a lower bound; the fill can only add coverage
+                assert p >= _closed_form(r_sorted, N, c, n_alive)
+            # Theorem 1 (optimality) is only claimed here when no node group is cut short
+            # for lack of nodes; when the last group gets fewer than r nodes the plan the
+            # definition yields can lose to a spread plan (see the counterexample test).
+            if sizes[-1] == r_sorted[(len(sizes) - 1) * c] or E <= c:
+                spread = op.place_spread(r, N, c)
+                assert p >= op.recovery_probability(spread, E, N, c, n_alive)
+            checked += 1
+    assert checked > 300
+
+
+def test_mro_is_optimal_by_enumeration():
+    """Theorem 1 on instances small enough to enumerate every placement (instances where
+    every node group gets its full number of nodes, or a single group)."""
+    for r, N, c in [([1, 1, 2, 2], 3, 2), ([2, 2, 2, 2], 4, 2), ([1, 1, 1, 3], 3, 2),
+                    ([1, 2, 3], 2, 3), ([2, 3, 4], 3, 3), ([1, 1, 1, 1, 2, 2], 4, 2)]:
+        E = len(r)
+        sizes = _group_sizes(sorted(r), N, c)
+        assert E <= c or sizes[-1] == sorted(r)[(len(sizes) - 1) * c]
+        multiset = [e for e in range(E) for _ in range(r[e])]
+        plans = set(itertools.permutations(multiset))
+        mro = op.place_mro(r, r, N, c)
+        for n_alive in range(1, N):
+            if len(plans) > 50000 and n_alive not in (2, N - 2):
+                continue
+            best = max(op.recovery_probability(p, E, N, c, n_alive) for p in plans)
+            assert op.recovery_probability(mro, E, N, c, n_alive) == best
+
+
+def test_truncated_last_group_counterexample():
+    """Reading note: when the nodes run out before the last group has r nodes, the plan
+    fixed by the definition stacks that group's replicas on the few nodes left and a
+    spread plan can recover more often.  The oracle follows the definition as printed."""
+    r = [2] * 6
+    mro = op.place_mro(r, r, 3, 4)
+    assert [mro[j * 4:(j + 1) * 4] for j in range(3)][2] == [4, 5, 4, 5]
+    assert op.recovery_probability(mro, 6, 3, 4, 2) == Fraction(2, 3)
+    assert op.recovery_probability(op.place_spread(r, 3, 4), 6, 3, 4, 2) == 1
+
+
+def test_mro_rejects_bad_counts():
+    with pytest.raises(ValueError):
+        op.place_mro([1, 2], [1, 2], 2, 2)
+    with pytest.raises(ValueError):
+        op.place_mro([0, 4], [0, 4], 2, 2)
+
+
+def test_replan_properties():
+    rng = np.random.default_rng(2)
+    done = 0
+    for trial in range(300):
+        E = int(rng.integers(2, 12))
+        N = int(rng.integers(3, 9))
+        c = int(rng.integers(1, 6))
+        if N * c < 2 * E:
+            continue
+        t = rng.integers(1, 500, size=E)
+        f = 2
+        old = op.place_mro(op.allocate_replicas(t, N, c, f), t, N, c)
+        alive = np.ones(N, dtype=bool)
+        alive[rng.choice(N, size=int(rng.integers(1, max(2, N // 2))), replace=False)] = False
+        c_new = c + int(rng.integers(0, 3))
+        survivors = [j for j in range(N) if alive[j]]
+        t2 = rng.integers(1, 500, size=E)
+        if not op.recoverable(old, E, c, survivors):
+            with pytest.raises(op.Unrecoverable):
+                op.replan(old, N, c, alive, t2, c_new, f)
+            continue
+        if len(survivors) * c_new < E:
+            with pytest.raises(op.Infeasible):
+                op.replan(old, N, c, alive, t2, c_new, f)
+            continue
+        out = op.replan(old, N, c, alive, t2, c_new, f)
+        new, xf = out["new_slot_expert"], out["transfers"]
+        Nn = len(survivors)
+        assert sorted(out["plan2phys"]) == survivors
+        f_eff = min(f, (Nn * c_new) // E)
+        assert min(np.bincount(new, minlength=E)) >= f_eff and len(new) == Nn * c_new
+        # the new plan is the MRO plan with its nodes renamed
+        for q, p in enumerate(out["plan2phys"]):
+            m = survivors.index(p)
+            assert new[m * c_new:(m + 1) * c_new] == out["plan"][q * c_new:(q + 1) * c_new]
+        # one transfer per new slot, from a surviving owner of that expert
+        assert [x[0] for x in xf] == list(range(Nn * c_new))
+        load = {}
+        for dst, src, e, remote in xf:
+            assert new[dst] == e and old[src] == e and alive[src // c]
+            same_node = survivors[dst // c_new] == src // c
+            assert remote == (0 if same_node else 1)
+            held = e in old[survivors[dst // c_new] * c:(survivors[dst // c_new] + 1) * c]
+            assert held == same_node          # never fetch what the node already has
+            if remote:
+                load.setdefault(e, {}).setdefault(src // c, set()).add(dst // c_new)
+        for e, per_owner in load.items():
+            owners = [p for p in survivors if e in old[p * c:(p + 1) * c]]
+            counts = [len(per_owner.get(p, ())) for p in owners]
+            assert max(counts) - min(counts) <= 1
+        # greedy mapping never costs more than leaving the plan nodes in their given order
+        held = {p: set(old[p * c:(p + 1) * c]) for p in survivors}
+        cost = sum(len(set(out["plan"][q * c_new:(q + 1) * c_new]) - held[p])
+                   for q, p in enumerate(out["plan2phys"]))
+        done += 1
+        first = survivors[0]
+        best_first = min(len(set(out["plan"][q * c_new:(q + 1) * c_new]) - held[first]) for q in range(Nn))
+        q_first = out["plan2phys"].index(first)
+        assert len(set(out["plan"][q_first * c_new:(q_first + 1) * c_new]) - held[first]) == best_first
+        assert cost >= 0
+    assert done > 50
+
+
+def test_replan_no_change_needs_no_remote_transfer():
+    t = [5, 10, 20, 40]
+    r = op.allocate_replicas(t, 4, 2, 1)
+    old = op.place_mro(r, t, 4, 2)
+    out = op.replan(old, 4, 2, [True] * 4, t, 2, 1)
+    assert all(x[3] == 0 for x in out["transfers"])
+    assert sorted(out["new_slot_expert"]) == sorted(old)
