@@ -1,0 +1,219 @@
+/*
+ * lazarus_moe.h -- C ABI of the MI355X (gfx950) implementation of the data-parallel hot
+ * path of the Lazarus MoE layer (Lazarus: Resilient and Elastic Training of
+ * Mixture-of-Experts Models, arXiv 2407.04656).
+ *
+ * One pass of the layer is five device calls on one stream
+ *
+ *     lz_route -> lz_plan_dispatch -> lz_permute -> lz_expert_ffn -> lz_unpermute_combine
+ *
+ * plus host-side planning (allocation, placement, re-planning after rank loss).  The N
+ * logical ranks of a placement plan live in one GPU's memory; no call communicates.
+ *
+ * Conventions
+ *   - Notation follows the paper: T tokens, d model dim, ffn hidden dim, E experts,
+ *     top-k, N ranks, c replica slots per rank, S = N*c slots, P = T*k pairs; a "pair"
+ *     is one (token t, choice kk) routing decision with pair index p = t*k + kk.
+ *   - A plan is slot_expert[S], slot id s = rank*c + local slot: the paper's placement
+ *     matrix (Appendix, proof of Theorem 1) read column by column.
+ *   - Every function returns an int32 status: LZ_OK or a negative LZ_E* code; nothing
+ *     throws.  lz_strerror() names a code.
+ *   - "dev" pointers are device (HBM) addresses, "host" pointers are ordinary host
+ *     memory.  The caller owns every buffer; the library allocates nothing and keeps no
+ *     state between calls.  Scratch comes from a caller-provided device workspace whose
+ *     size lz_*_workspace_bytes() reports.
+ *   - Device calls are enqueued on `stream` (a hipStream_t passed as void*, NULL = the
+ *     default stream), return without waiting, and never synchronise with the host.
+ *     Arguments that can be checked on the host are; data-dependent problems (an id out
+ *     of range, an expert without a replica) are flagged in an optional device status
+ *     word and never cause an out-of-bounds access.
+ *   - All matrices are row-major and dense.  dtype LZ_BF16 tensors hold bfloat16 bit
+ *     patterns; accumulation is always fp32.
+ *   - Limits: 1 <= k <= min(E, 8), E <= 256, N <= 64, c <= 64, P = T*k < 2^31 / max(d, ffn).
+ */
+#ifndef LAZARUS_MOE_H
+#define LAZARUS_MOE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+  LZ_OK = 0,
+  LZ_EINVAL = -1,        /* null pointer / value out of the documented range          */
+  LZ_ESHAPE = -2,        /* shape outside the limits above or not supported by a path  */
+  LZ_EWORKSPACE = -3,    /* workspace missing, misaligned (256 B) or too small         */
+  LZ_EUNRECOVERABLE = -4,/* an expert has no replica on any surviving rank (Sec. 4.3)  */
+  LZ_EINFEASIBLE = -5,   /* fewer slots than experts                                   */
+  LZ_EHIP = -6           /* a HIP runtime call failed (launch error)                   */
+};
+
+enum { LZ_F32 = 0, LZ_BF16 = 1 };
+enum { LZ_GELU = 0, LZ_SWIGLU = 1 };
+
+/* bits of the device status word written by lz_plan_dispatch */
+enum {
+  LZ_PLAN_UNCOVERED_EXPERT = 1,  /* an expert received tokens but the plan holds no replica */
+  LZ_PLAN_BAD_EXPERT_ID = 2,     /* a top-k id or a slot_expert entry outside [0, E)        */
+  LZ_PLAN_BAD_RANK_SPLIT = 4     /* rank_tok_off not ascending from 0 to T                  */
+};
+
+typedef struct {
+  int32_t T, d, ffn, E, k, N, c;
+  int32_t dtype; /* LZ_F32 | LZ_BF16: type of x, xp, hidden, yp, y and the weights */
+  int32_t act;   /* LZ_GELU | LZ_SWIGLU */
+} lz_shape;
+
+const char* lz_strerror(int32_t code);
+int32_t lz_version(void);
+
+/* Bytes of device workspace (256-byte aligned) lz_plan_dispatch / lz_expert_ffn need
+ * for this shape; 0 if the shape is invalid. */
+size_t lz_plan_workspace_bytes(const lz_shape* shape);
+size_t lz_ffn_workspace_bytes(const lz_shape* shape);
+
+/* ---------------------------------------------------------------- device hot path */
+
+/* Top-k gate routing (Sec. 2.1: the gate network routes each token to its top-k
+ * experts).  For every token: the k largest of its E fp32 logits in descending order,
+ * equal logits towards the lower expert index (-0.0 == +0.0); gates = softmax over
+ * those k logits in fp32 (they sum to 1).  Logits must be finite.
+ *   logits      dev [T,E] f32 (in)      topk_ids   dev [T,k] i32 (out)
+ *   topk_gates  dev [T,k] f32 (out)
+ * T == 0 is a no-op. */
+int32_t lz_route(const float* logits, int32_t T, int32_t E, int32_t k,
+                 int32_t* topk_ids, float* topk_gates, void* stream);
+
+/* The flexible token dispatcher's schedule (Algorithm 1, Sec. 4.2) for all source ranks
+ * at once, and the row maps of the per-slot contiguous buffers.
+ *   1. Tej[e,i]: pairs routed to expert e whose token lies on rank i, rank i owning
+ *      tokens [rank_tok_off[i], rank_tok_off[i+1])  (the algorithm's T_{e,j}; the
+ *      all-gather of Sec. 4.2 is unnecessary in one address space).
+ *   2. D[e,i,j]: pairs of e that rank i sends to rank j.  Integer reading of the
+ *      algorithm: capacity cap[e,j] = floor(hi*t_e/r_e) - floor(lo*t_e/r_e) with lo/hi
+ *      the running replica count before/after rank j; each rank keeps min(cap, Tej)
+ *      (local tokens first); its overflow is spread over the other ranks in proportion
+ *      to their residual capacity, cumulatively floored so every row of D sums to Tej.
+ *   3. Row maps (the algorithm's reshuffle, extended to the receive side): rank i's
+ *      pairs of e go, in token order, to destinations in ascending j; the (e,j) receive
+ *      list is the concatenation over ascending i and is cut over the R[e,j] slots of
+ *      rank j holding e (ascending slot id), slot m taking positions
+ *      [floor(m*n/R), floor((m+1)*n/R)).  Rows are numbered slot after slot.
+ * The result is deterministic (no order-dependent atomics).
+ *   topk_ids     dev [T,k] i32 (in)       rank_tok_off dev [N+1] i32 (in)
+ *   slot_expert  dev [S] i32 (in)
+ *   slot_counts  dev [S] i32 (out)        slot_offsets dev [S+1] i32 (out, exclusive scan)
+ *   pair_to_row  dev [P] i32 (out; -1 for a pair that could not be placed)
+ *   row_to_pair  dev [P] i32 (out; inverse map, -1 for an unused row)
+ *   Tej_opt      dev [E,N] i32 or NULL    D_opt dev [E,N,N] i32 or NULL (out, optional)
+ *   status_opt   dev [1] i32 or NULL (out: 0 or LZ_PLAN_* bits)
+ *   ws           dev workspace of >= lz_plan_workspace_bytes(shape) bytes */
+int32_t lz_plan_dispatch(const int32_t* topk_ids, const lz_shape* shape,
+                         const int32_t* rank_tok_off, const int32_t* slot_expert,
+                         int32_t* slot_counts, int32_t* slot_offsets,
+                         int32_t* pair_to_row, int32_t* row_to_pair,
+                         int32_t* Tej_opt, int32_t* D_opt, int32_t* status_opt,
+                         void* ws, size_t ws_bytes, void* stream);
+
+/* Reshuffle into per-slot contiguous buffers (Algorithm 1's h -> h'):
+ * xp[row,:] = x[row_to_pair[row] / k, :]; rows whose map entry is outside [0,P) are
+ * zero-filled.  x dev [T,d], xp dev [P,d], both of shape->dtype. */
+int32_t lz_permute(const void* x, const int32_t* row_to_pair, const lz_shape* shape,
+                   void* xp, void* stream);
+
+/* Expert FFN over the permuted buffer (Sec. 2.1: experts are parallel FFNs; each replica
+ * processes the tokens dispatched to it).  Rows [slot_offsets[s], slot_offsets[s+1]) use
+ * the weights of slot s:
+ *   LZ_GELU    yp = gelu(xp W1^T) W2^T          gelu exact: 0.5 v (1 + erf(v/sqrt 2))
+ *   LZ_SWIGLU  yp = (silu(xp Wg^T) * (xp Wu^T)) W2^T
+ *   w1  dev [S, n1, d]   n1 = ffn (GELU) or 2*ffn (SwiGLU: rows [0,ffn) = Wg, [ffn,2ffn) = Wu)
+ *   w2  dev [S, d, ffn]
+ * Every slot owns its own copy of its expert's weights (replicas are separate buffers).
+ * The hidden activation is kept in shape->dtype in the workspace; products accumulate
+ * in fp32.  LZ_BF16 uses MFMA kernels when d % 256 == 0 and ffn % 128 == 0 (ffn % 256 for
+ * GELU) and a generic tiled kernel otherwise; LZ_F32 always uses the generic kernel.
+ * slot_offsets is read on the device only; offsets outside [0,P] are clipped.
+ *   xp dev [P,d] (in), yp dev [P,d] (out), ws >= lz_ffn_workspace_bytes(shape). */
+int32_t lz_expert_ffn(const void* xp, const int32_t* slot_offsets,
+                      const void* w1, const void* w2, const lz_shape* shape,
+                      void* yp, void* ws, size_t ws_bytes, void* stream);
+
+/* Inverse permutation and gate-weighted combine (Sec. 2.1, the second all-to-all and the
+ * combine): y[t,:] = sum_{kk<k} topk_gates[t,kk] * yp[pair_to_row[t*k+kk], :], summed in
+ * fp32 in ascending kk and rounded once; a pair whose row is outside [0,P) contributes 0.
+ *   yp dev [P,d], pair_to_row dev [P] i32, topk_gates dev [T,k] f32, y dev [T,d]. */
+int32_t lz_unpermute_combine(const void* yp, const int32_t* pair_to_row,
+                             const float* topk_gates, const lz_shape* shape,
+                             void* y, void* stream);
+
+/* ---------------------------------------------------------------- host planning */
+
+/* Replica allocation, Eq. 1 (Sec. 4.1): experts in ascending load t_e (ties: lower id)
+ * get r_e = max(floor(t_e / sum_{e'>=e} t_e' * (N*c - sum_{e'<e} r_e')), f).  If the
+ * remaining loads are all zero the remaining slots are split evenly; if N*c < E*f the
+ * threshold is relaxed to floor(N*c/E).  Guarantees sum r_e = N*c, r_e >= f_eff and r_e
+ * non-decreasing in load order.  All pointers host.  LZ_EINFEASIBLE if N*c < E. */
+int32_t lz_allocate_replicas(const int64_t* t_e, int32_t E, int32_t N, int32_t c,
+                             int32_t f, int32_t* r_e /* [E] out */);
+
+/* Maximum-rank-overlap placement (Sec. 4.1; definition in Theorem 1).  Experts ordered by
+ * (r_e, t_e, id) ascending are cut into ceil(E/c) groups of c; node group g takes the
+ * next r_{first expert of g} ranks (the last group at most what is left) and each of its
+ * ranks holds one replica of every expert of the group; if E <= c expert e also sits on
+ * each of the first min(r_e,N) ranks.  Vacant slots, walked by (rank, local slot), take
+ * the remaining replicas round-robin over the experts in that order.  sum r_e must equal
+ * N*c and every r_e >= 1 (else LZ_EINVAL).  All pointers host. */
+int32_t lz_place_mro(const int32_t* r_e, const int64_t* t_e, int32_t E, int32_t N,
+                     int32_t c, int32_t* slot_expert /* [N*c] out */);
+
+/* Spread baseline (Sec. 6.3): the q-th replica, listed expert after expert, goes to rank
+ * q mod N, local slot q div N.  All pointers host. */
+int32_t lz_place_spread(const int32_t* r_e, int32_t E, int32_t N, int32_t c,
+                        int32_t* slot_expert /* [N*c] out */);
+
+/* Probability that n_alive uniformly drawn alive ranks still hold every expert, by
+ * enumerating all C(N, n_alive) sets (Sec. 6.3; the objective of Theorem 1).  Writes the
+ * count of recoverable sets and the total.  N <= 62.  All pointers host. */
+int32_t lz_recovery_probability(const int32_t* slot_expert, int32_t E, int32_t N, int32_t c,
+                                int32_t n_alive, uint64_t* n_recoverable, uint64_t* n_total);
+
+typedef struct {
+  int32_t dst_slot; /* slot in the NEW plan (rank m = m-th surviving rank)            */
+  int32_t src_slot; /* slot in the OLD plan whose weights are copied                  */
+  int32_t expert;
+  int32_t remote;   /* 1 if the source lies on another rank (a network fetch), else 0 */
+} lz_transfer;
+
+/* Re-plan after rank loss (Sec. 4.3).  survivors = ranks with alive[j] != 0, ascending.
+ * LZ_EUNRECOVERABLE if some expert has no replica on a survivor.  Otherwise: Eq. 1 on
+ * N_new*c_new slots, MRO placement, then the greedy node mapping (each physical survivor,
+ * in ascending id, takes the unused plan node with the fewest experts it does not already
+ * hold; lowest plan node on ties) and one transfer per new slot: from the rank's own
+ * lowest old slot of that expert if it held one, else from a surviving owner, the
+ * requests for one expert dealt round-robin over its owners in ascending rank, one fetch
+ * per (rank, expert).
+ *   old_slot_expert host [N_old*c_old]   alive host [N_old] (u8)   t_e host [E]
+ *   new_slot_expert host [N_new*c_new] out      plan2phys host [N_new] out
+ *   xfers host [*n_xfers capacity] out; *n_xfers in: capacity (>= N_new*c_new), out: count
+ *   N_new_out host [1] out */
+int32_t lz_replan(const int32_t* old_slot_expert, int32_t N_old, int32_t c_old,
+                  const uint8_t* alive, const int64_t* t_e, int32_t E, int32_t c_new,
+                  int32_t f, int32_t* new_slot_expert, int32_t* plan2phys,
+                  lz_transfer* xfers, int32_t* n_xfers, int32_t* N_new_out);
+
+/* Carry out a transfer list on the device: for each entry copy the source slot's w1 and
+ * w2 blocks from the old weight buffers into the destination slot of the new ones
+ * (device-to-device copies on `stream`; stands in for the batched send/recv of Sec. 5).
+ *   xfers host [n]; w1_old/w2_old dev [S_old,...]; w1_new/w2_new dev [S_new,...]. */
+int32_t lz_apply_transfers(const lz_transfer* xfers, int32_t n,
+                           const void* w1_old, const void* w2_old, int32_t S_old,
+                           void* w1_new, void* w2_new, int32_t S_new,
+                           const lz_shape* shape, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LAZARUS_MOE_H */

@@ -1,0 +1,337 @@
+"""ctypes binding with the same names as the C ABI (argument marshalling only)."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+
+import numpy as np
+
+__all__ = [
+    "LZ_F32", "LZ_BF16", "LZ_GELU", "LZ_SWIGLU", "LzError", "Shape", "lib", "lib_path",
+    "lz_strerror", "lz_version", "lz_plan_workspace_bytes", "lz_ffn_workspace_bytes",
+    "lz_route", "lz_plan_dispatch", "lz_permute", "lz_expert_ffn", "lz_unpermute_combine",
+    "lz_allocate_replicas", "lz_place_mro", "lz_place_spread", "lz_recovery_probability",
+    "lz_replan", "lz_apply_transfers", "MoELayer",
+]
+
+LZ_F32, LZ_BF16 = 0, 1
+LZ_GELU, LZ_SWIGLU = 0, 1
+LZ_OK, LZ_EINVAL, LZ_ESHAPE, LZ_EWORKSPACE, LZ_EUNRECOVERABLE, LZ_EINFEASIBLE, LZ_EHIP = 0, -1, -2, -3, -4, -5, -6
+
+
+class LzError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        super().__init__(f"{where}: {lz_strerror(code)} ({code})")
+
+
+class _Shape(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("T", "d", "ffn", "E", "k", "N", "c", "dtype", "act")]
+
+
+class _Transfer(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("dst_slot", "src_slot", "expert", "remote")]
+
+
+@dataclass(frozen=True)
+class Shape:
+    T: int
+    d: int
+    ffn: int
+    E: int
+    k: int
+    N: int
+    c: int
+    dtype: int
+    act: int
+
+    @property
+    def S(self):
+        return self.N * self.c
+
+    @property
+    def P(self):
+        return self.T * self.k
+
+    def c_struct(self):
+        return _Shape(self.T, self.d, self.ffn, self.E, self.k, self.N, self.c, self.dtype, self.act)
+
+    @staticmethod
+    def from_config(cfg):
+        return Shape(cfg.T, cfg.d, cfg.ffn, cfg.E, cfg.k, cfg.N, cfg.c,
+                     LZ_F32 if cfg.dtype == "f32" else LZ_BF16,
+                     LZ_GELU if cfg.act == "gelu" else LZ_SWIGLU)
+
+
+def lib_path() -> str:
+    return os.path.join(os.path.dirname(os.path.abspath(__file__)), "liblazarus_moe.so")
+
+
+def _load():
+    path = lib_path()
+    if not os.path.exists(path):
+        raise ImportError(
+            f"{path} is missing: build it first (python paper_2407_04656_amd/build.py or "
+            "__graft_entry__.build()); there is no fallback path")
+    L = C.CDLL(path)
+    vp, i32, u64 = C.c_void_p, C.c_int32, C.c_size_t
+    sp = C.POINTER(_Shape)
+    sig = {
+        "lz_strerror": (C.c_char_p, [i32]),
+        "lz_version": (i32, []),
+        "lz_plan_workspace_bytes": (u64, [sp]),
+        "lz_ffn_workspace_bytes": (u64, [sp]),
+        "lz_route": (i32, [vp, i32, i32, i32, vp, vp, vp]),
+        "lz_plan_dispatch": (i32, [vp, sp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, u64, vp]),
+        "lz_permute": (i32, [vp, vp, sp, vp, vp]),
+        "lz_expert_ffn": (i32, [vp, vp, vp, vp, sp, vp, vp, u64, vp]),
+        "lz_unpermute_combine": (i32, [vp, vp, vp, sp, vp, vp]),
+        "lz_allocate_replicas": (i32, [vp, i32, i32, i32, i32, vp]),
+        "lz_place_mro": (i32, [vp, vp, i32, i32, i32, vp]),
+        "lz_place_spread": (i32, [vp, i32, i32, i32, vp]),
+        "lz_recovery_probability": (i32, [vp, i32, i32, i32, i32, vp, vp]),
+        "lz_replan": (i32, [vp, i32, i32, vp, vp, i32, i32, i32, vp, vp, vp, vp, vp]),
+        "lz_apply_transfers": (i32, [vp, i32, vp, vp, i32, vp, vp, i32, sp, vp]),
+    }
+    for name, (res, args) in sig.items():
+        fn = getattr(L, name)
+        fn.restype, fn.argtypes = res, args
+    return L
+
+
+lib = _load()
+EXPORTS = ["lz_strerror", "lz_version", "lz_plan_workspace_bytes", "lz_ffn_workspace_bytes", "lz_route",
+           "lz_plan_dispatch", "lz_permute", "lz_expert_ffn", "lz_unpermute_combine",
+           "lz_allocate_replicas", "lz_place_mro", "lz_place_spread", "lz_recovery_probability",
+           "lz_replan", "lz_apply_transfers"]
+
+
+def lz_strerror(code: int) -> str:
+    return lib.lz_strerror(int(code)).decode()
+
+
+def lz_version() -> int:
+    return int(lib.lz_version())
+
+
+def _check(code: int, where: str):
+    if code != LZ_OK:
+        raise LzError(code, where)
+
+
+def _ptr(t):
+    """Device (or host) address of a torch tensor / numpy array, None -> NULL."""
+    if t is None:
+        return None
+    if isinstance(t, np.ndarray):
+        assert t.flags["C_CONTIGUOUS"]
+        return t.ctypes.data
+    assert t.is_contiguous()
+    return t.data_ptr()
+
+
+def _stream():
+    import torch
+    return torch.cuda.current_stream().cuda_stream
+
+
+def lz_plan_workspace_bytes(shape: Shape) -> int:
+    return int(lib.lz_plan_workspace_bytes(C.byref(shape.c_struct())))
+
+
+def lz_ffn_workspace_bytes(shape: Shape) -> int:
+    return int(lib.lz_ffn_workspace_bytes(C.byref(shape.c_struct())))
+
+
+# ------------------------------------------------------------------ device hot path
+def lz_route(logits, T, E, k, topk_ids, topk_gates, stream=None):
+    _check(lib.lz_route(_ptr(logits), T, E, k, _ptr(topk_ids), _ptr(topk_gates),
+                        _stream() if stream is None else stream), "lz_route")
+
+
+def lz_plan_dispatch(topk_ids, shape, rank_tok_off, slot_expert, slot_counts, slot_offsets, pair_to_row,
+                     row_to_pair, Tej_opt, D_opt, status_opt, ws, ws_bytes, stream=None):
+    _check(lib.lz_plan_dispatch(_ptr(topk_ids), C.byref(shape.c_struct()), _ptr(rank_tok_off),
+                                _ptr(slot_expert), _ptr(slot_counts), _ptr(slot_offsets),
+                                _ptr(pair_to_row), _ptr(row_to_pair), _ptr(Tej_opt), _ptr(D_opt),
+                                _ptr(status_opt), _ptr(ws), ws_bytes,
+                                _stream() if stream is None else stream), "lz_plan_dispatch")
+
+
+def lz_permute(x, row_to_pair, shape, xp, stream=None):
+    _check(lib.lz_permute(_ptr(x), _ptr(row_to_pair), C.byref(shape.c_struct()), _ptr(xp),
+                          _stream() if stream is None else stream), "lz_permute")
+
+
+def lz_expert_ffn(xp, slot_offsets, w1, w2, shape, yp, ws, ws_bytes, stream=None):
+    _check(lib.lz_expert_ffn(_ptr(xp), _ptr(slot_offsets), _ptr(w1), _ptr(w2), C.byref(shape.c_struct()),
+                             _ptr(yp), _ptr(ws), ws_bytes,
+                             _stream() if stream is None else stream), "lz_expert_ffn")
+
+
+def lz_unpermute_combine(yp, pair_to_row, topk_gates, shape, y, stream=None):
+    _check(lib.lz_unpermute_combine(_ptr(yp), _ptr(pair_to_row), _ptr(topk_gates),
+                                    C.byref(shape.c_struct()), _ptr(y),
+                                    _stream() if stream is None else stream), "lz_unpermute_combine")
+
+
+# ------------------------------------------------------------------ host planning
+def _i64(a):
+    return np.ascontiguousarray(np.asarray(a, dtype=np.int64))
+
+
+def _i32(a):
+    return np.ascontiguousarray(np.asarray(a, dtype=np.int32))
+
+
+def lz_allocate_replicas(t_e, N, c, f):
+    t = _i64(t_e)
+    r = np.zeros(len(t), dtype=np.int32)
+    _check(lib.lz_allocate_replicas(t.ctypes.data, len(t), N, c, f, r.ctypes.data), "lz_allocate_replicas")
+    return r
+
+
+def lz_place_mro(r_e, t_e, N, c):
+    r, t = _i32(r_e), _i64(t_e)
+    out = np.full(N * c, -1, dtype=np.int32)
+    _check(lib.lz_place_mro(r.ctypes.data, t.ctypes.data, len(r), N, c, out.ctypes.data), "lz_place_mro")
+    return out
+
+
+def lz_place_spread(r_e, N, c):
+    r = _i32(r_e)
+    out = np.full(N * c, -1, dtype=np.int32)
+    _check(lib.lz_place_spread(r.ctypes.data, len(r), N, c, out.ctypes.data), "lz_place_spread")
+    return out
+
+
+def lz_recovery_probability(slot_expert, E, N, c, n_alive):
+    se = _i32(slot_expert)
+    good, total = C.c_uint64(0), C.c_uint64(0)
+    _check(lib.lz_recovery_probability(se.ctypes.data, E, N, c, n_alive, C.addressof(good),
+                                       C.addressof(total)), "lz_recovery_probability")
+    return good.value, total.value
+
+
+def lz_replan(old_slot_expert, N_old, c_old, alive, t_e, c_new, f):
+    old, t = _i32(old_slot_expert), _i64(t_e)
+    al = np.ascontiguousarray(np.asarray(alive, dtype=np.uint8))
+    n_max = int(al.astype(bool).sum())
+    new = np.full(max(1, n_max * c_new), -1, dtype=np.int32)
+    plan2phys = np.full(max(1, n_max), -1, dtype=np.int32)
+    xf = (_Transfer * max(1, n_max * c_new))()
+    n_x = C.c_int32(n_max * c_new)
+    n_new = C.c_int32(0)
+    _check(lib.lz_replan(old.ctypes.data, N_old, c_old, al.ctypes.data, t.ctypes.data, len(t), c_new, f,
+                         new.ctypes.data, plan2phys.ctypes.data, C.addressof(xf), C.addressof(n_x),
+                         C.addressof(n_new)), "lz_replan")
+    transfers = [(x.dst_slot, x.src_slot, x.expert, x.remote) for x in xf[:n_x.value]]
+    return {"new_slot_expert": new[:n_new.value * c_new], "plan2phys": plan2phys[:n_new.value],
+            "transfers": transfers, "N_new": n_new.value}
+
+
+def lz_apply_transfers(transfers, w1_old, w2_old, S_old, w1_new, w2_new, S_new, shape, stream=None):
+    arr = (_Transfer * max(1, len(transfers)))()
+    for i, (d, s, e, r) in enumerate(transfers):
+        arr[i] = _Transfer(d, s, e, r)
+    _check(lib.lz_apply_transfers(C.addressof(arr), len(transfers), _ptr(w1_old), _ptr(w2_old), S_old,
+                                  _ptr(w1_new), _ptr(w2_new), S_new, C.byref(shape.c_struct()),
+                                  _stream() if stream is None else stream), "lz_apply_transfers")
+
+
+# ------------------------------------------------------------------ convenience
+class MoELayer:
+    """Owns the device buffers of one layer shape and runs the five calls in order.
+
+    Buffer management only: torch allocates, the library computes.  Weights are per-slot
+    copies laid out as w1[S, n1, d], w2[S, d, ffn] (see include/lazarus_moe.h).
+    """
+
+    def __init__(self, shape: Shape, device="cuda:0"):
+        import torch
+        self.shape = shape
+        self.device = torch.device(device)
+        s = shape
+        tdt = torch.float32 if s.dtype == LZ_F32 else torch.bfloat16
+        dev = self.device
+        i32 = torch.int32
+        self.topk_ids = torch.empty((s.T, s.k), dtype=i32, device=dev)
+        self.topk_gates = torch.empty((s.T, s.k), dtype=torch.float32, device=dev)
+        self.slot_counts = torch.empty(s.S, dtype=i32, device=dev)
+        self.slot_offsets = torch.empty(s.S + 1, dtype=i32, device=dev)
+        self.pair_to_row = torch.empty(s.P, dtype=i32, device=dev)
+        self.row_to_pair = torch.empty(s.P, dtype=i32, device=dev)
+        self.Tej = torch.empty((s.E, s.N), dtype=i32, device=dev)
+        self.D = torch.empty((s.E, s.N, s.N), dtype=i32, device=dev)
+        self.status = torch.zeros(1, dtype=i32, device=dev)
+        self.xp = torch.empty((s.P, s.d), dtype=tdt, device=dev)
+        self.yp = torch.empty((s.P, s.d), dtype=tdt, device=dev)
+        self.y = torch.empty((s.T, s.d), dtype=tdt, device=dev)
+        self.plan_ws_bytes = lz_plan_workspace_bytes(shape)
+        self.ffn_ws_bytes = lz_ffn_workspace_bytes(shape)
+        self.plan_ws = torch.empty(self.plan_ws_bytes, dtype=torch.uint8, device=dev)
+        self.ffn_ws = torch.empty(self.ffn_ws_bytes, dtype=torch.uint8, device=dev)
+        self.rank_tok_off = None
+        self.slot_expert = None
+        self.w1 = None
+        self.w2 = None
+
+    def set_plan(self, slot_expert, rank_tok_off):
+        import torch
+        self.slot_expert = torch.as_tensor(np.asarray(slot_expert, dtype=np.int32), device=self.device)
+        self.rank_tok_off = torch.as_tensor(np.asarray(rank_tok_off, dtype=np.int32), device=self.device)
+
+    def set_slot_weights(self, w1, w2):
+        self.w1, self.w2 = w1, w2
+
+    def load_expert_weights(self, w1_experts, w2_experts, slot_expert):
+        """Give every slot its own copy of its expert's weights (host arrays indexed by expert)."""
+        import torch
+        s = self.shape
+        tdt = torch.float32 if s.dtype == LZ_F32 else torch.bfloat16
+
+        def to_dev(a):
+            t = torch.from_numpy(a)
+            if s.dtype == LZ_BF16:
+                t = t.view(torch.bfloat16)
+            return t.to(self.device)
+
+        n1 = w1_experts.shape[1]
+        self.w1 = torch.empty((s.S, n1, s.d), dtype=tdt, device=self.device)
+        self.w2 = torch.empty((s.S, s.d, s.ffn), dtype=tdt, device=self.device)
+        cache = {}
+        for slot, e in enumerate(np.asarray(slot_expert)):
+            e = int(e)
+            if e not in cache:
+                cache[e] = (to_dev(w1_experts[e]), to_dev(w2_experts[e]))
+            self.w1[slot].copy_(cache[e][0])
+            self.w2[slot].copy_(cache[e][1])
+
+    # the five calls
+    def route(self, logits):
+        s = self.shape
+        lz_route(logits, s.T, s.E, s.k, self.topk_ids, self.topk_gates)
+
+    def plan_dispatch(self):
+        lz_plan_dispatch(self.topk_ids, self.shape, self.rank_tok_off, self.slot_expert, self.slot_counts,
+                         self.slot_offsets, self.pair_to_row, self.row_to_pair, self.Tej, self.D,
+                         self.status, self.plan_ws, self.plan_ws_bytes)
+
+    def permute(self, x):
+        lz_permute(x, self.row_to_pair, self.shape, self.xp)
+
+    def expert_ffn(self):
+        lz_expert_ffn(self.xp, self.slot_offsets, self.w1, self.w2, self.shape, self.yp, self.ffn_ws,
+                      self.ffn_ws_bytes)
+
+    def unpermute_combine(self):
+        lz_unpermute_combine(self.yp, self.pair_to_row, self.topk_gates, self.shape, self.y)
+
+    def forward(self, logits, x):
+        self.route(logits)
+        self.plan_dispatch()
+        self.permute(x)
+        self.expert_ffn()
+        self.unpermute_combine()
+        return self.y

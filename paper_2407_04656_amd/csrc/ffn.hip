@@ -1,0 +1,473 @@
+// Expert FFN as a grouped GEMM over the per-slot row ranges (Sec. 2.1: experts are
+// parallel FFNs; every replica processes the rows dispatched to its slot).
+//
+//   GEMM-1   hidden[P, ffn] = act(xp[P, d] * W1[slot]^T)      act = GELU | SwiGLU, fused
+//   GEMM-2   yp[P, d]       = hidden[P, ffn] * W2[slot]^T
+//
+// Group sizes are data dependent and only known on the device, so a one-workgroup kernel
+// first turns slot_offsets into a table of row tiles (slot, first row, end row); the GEMM
+// grid is sized for the worst case and surplus workgroups exit.
+//
+// bf16 path (gfx950 MFMA): 256x256x64 workgroup tile, 4 waves in 2x2, each wave a 128x128
+// patch = 4x4 v_mfma_f32_32x32x16_bf16 accumulators (fp32).  Both operands are K-contiguous
+// and are streamed HBM -> LDS with 16-byte buffer loads that write LDS directly, double
+// buffered; the XOR swizzle that keeps the ds_read_b128 fragment reads conflict-free is
+// applied on the global-address side because a direct-to-LDS load fixes the LDS side to
+// lane order.  Buffer descriptors bound every load, so ragged tiles cannot fault.  The
+// MFMA takes the weight fragment as its row operand, which leaves each lane with 4
+// consecutive output columns per accumulator group: 8-byte bf16 stores, no LDS transpose.
+// For SwiGLU the weight tile interleaves 32-row fragments of Wg and Wu, so the gate and up
+// values of one output element sit in the same lane and register index.
+//
+// Generic path (fp32 tensors, or bf16 shapes the MFMA tiling does not divide): a plain
+// 64x64x16 LDS-tiled kernel with fp32 FMA accumulation and full bounds checks.
+#include "lz_common.h"
+
+namespace {
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
+
+constexpr int kTileHeader = 64;  // ints before the tile arrays; [0] = number of row tiles
+constexpr int kGroupM = 4;       // row tiles that share a run of column tiles (L2 reuse)
+
+enum { EPI_NONE = 0, EPI_GELU = 1, EPI_SWIGLU = 2 };
+
+struct TileTable {
+  int32_t* header;
+  int32_t* slot;
+  int32_t* row0;
+  int32_t* row_end;
+  int capacity;
+};
+
+inline int tile_capacity(long long P, int S, int BM) {
+  long long n = (P + BM - 1) / BM + S;
+  return int((n + kGroupM - 1) / kGroupM * kGroupM);
+}
+
+inline size_t tile_table_bytes(long long P, int S, int BM) {
+  return lz::align256(sizeof(int32_t) * (kTileHeader + 3 * (size_t)tile_capacity(P, S, BM)));
+}
+
+inline TileTable carve_tiles(void* base, long long P, int S, int BM) {
+  TileTable t;
+  t.capacity = tile_capacity(P, S, BM);
+  t.header = (int32_t*)base;
+  t.slot = t.header + kTileHeader;
+  t.row0 = t.slot + t.capacity;
+  t.row_end = t.row0 + t.capacity;
+  return t;
+}
+
+// slot_offsets -> row tiles.  Offsets are clipped to [0, P] and made non-decreasing.
+__global__ __launch_bounds__(256) void build_tiles_kernel(const int32_t* __restrict__ slot_offsets,
+                                                          int S, long long P, int BM, TileTable t) {
+  __shared__ int s_first[lz::kMaxN * lz::kMaxC + 1];
+  if (threadIdx.x == 0) {
+    int running = 0;
+    for (int s = 0; s < S; ++s) {
+      long long a = slot_offsets[s], b = slot_offsets[s + 1];
+      a = a < 0 ? 0 : (a > P ? P : a);
+      b = b < a ? a : (b > P ? P : b);
+      s_first[s] = running;
+      running += int((b - a + BM - 1) / BM);
+      if (running > t.capacity) running = t.capacity;
+    }
+    s_first[S] = running;
+    t.header[0] = running;
+  }
+  __syncthreads();
+  for (int s = threadIdx.x; s < S; s += blockDim.x) {
+    long long a = slot_offsets[s], b = slot_offsets[s + 1];
+    a = a < 0 ? 0 : (a > P ? P : a);
+    b = b < a ? a : (b > P ? P : b);
+    for (int i = s_first[s]; i < s_first[s + 1]; ++i) {
+      t.slot[i] = s;
+      t.row0[i] = int(a + (long long)(i - s_first[s]) * BM);
+      t.row_end[i] = int(b);
+    }
+  }
+}
+
+__device__ __forceinline__ float gelu_exact(float v) {
+  return 0.5f * v * (1.0f + erff(v * 0.70710678118654752440f));
+}
+__device__ __forceinline__ float silu(float v) { return v / (1.0f + expf(-v)); }
+
+// ------------------------------------------------------------------------------------------
+// generic tiled kernel
+// ------------------------------------------------------------------------------------------
+template <typename Elem>
+__device__ __forceinline__ float load_elem(const Elem* p);
+template <>
+__device__ __forceinline__ float load_elem<float>(const float* p) { return *p; }
+template <>
+__device__ __forceinline__ float load_elem<uint16_t>(const uint16_t* p) { return lz::bf16_to_f32(*p); }
+template <typename Elem>
+__device__ __forceinline__ void store_elem(Elem* p, float v);
+template <>
+__device__ __forceinline__ void store_elem<float>(float* p, float v) { *p = v; }
+template <>
+__device__ __forceinline__ void store_elem<uint16_t>(uint16_t* p, float v) { *p = lz::f32_to_bf16(v); }
+
+// C[rows of the tile, n] = epi( sum_k A[row, k] * W[slot][n (+ n_up), k] )
+template <typename Elem, int EPI>
+__global__ __launch_bounds__(256) void gemm_generic_kernel(const Elem* __restrict__ A, int K,
+                                                           const Elem* __restrict__ W,
+                                                           size_t w_slot_stride, int n_out, int up_row0,
+                                                           Elem* __restrict__ C, TileTable t) {
+  constexpr int BM = 64, BN = 64, BK = 16;
+  constexpr bool DUAL = EPI == EPI_SWIGLU;
+  __shared__ float sA[BK][BM + 1];
+  __shared__ float sB[DUAL ? 2 : 1][BK][BN + 1];
+  const int tile = blockIdx.y;
+  if (tile >= t.header[0]) return;
+  const int slot = t.slot[tile], row0 = t.row0[tile], row_end = t.row_end[tile];
+  const int n0 = blockIdx.x * BN;
+  const Elem* Ws = W + (size_t)slot * w_slot_stride;
+  const int tx = threadIdx.x % 16, ty = threadIdx.x / 16;
+  float acc[4][4] = {}, acc_up[4][4] = {};
+  for (int k0 = 0; k0 < K; k0 += BK) {
+    for (int i = threadIdx.x; i < BM * BK; i += 256) {
+      const int r = i / BK, kk = i % BK;
+      const int row = row0 + r;
+      sA[kk][r] = (row < row_end && k0 + kk < K) ? load_elem<Elem>(A + (size_t)row * K + k0 + kk) : 0.f;
+      const int n = n0 + r;
+      const bool ok = n < n_out && k0 + kk < K;
+      sB[0][kk][r] = ok ? load_elem<Elem>(Ws + (size_t)n * K + k0 + kk) : 0.f;
+      if (DUAL) sB[DUAL ? 1 : 0][kk][r] = ok ? load_elem<Elem>(Ws + (size_t)(up_row0 + n) * K + k0 + kk) : 0.f;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int kk = 0; kk < BK; ++kk) {
+      float a[4], b[4], bu[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        a[i] = sA[kk][ty * 4 + i];
+        b[i] = sB[0][kk][tx * 4 + i];
+        bu[i] = DUAL ? sB[DUAL ? 1 : 0][kk][tx * 4 + i] : 0.f;
+      }
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          acc[i][j] = fmaf(a[i], b[j], acc[i][j]);
+          if (DUAL) acc_up[i][j] = fmaf(a[i], bu[j], acc_up[i][j]);
+        }
+    }
+    __syncthreads();
+  }
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int row = row0 + ty * 4 + i;
+    if (row >= row_end) continue;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int n = n0 + tx * 4 + j;
+      if (n >= n_out) continue;
+      float v = acc[i][j];
+      if (EPI == EPI_GELU) v = gelu_exact(v);
+      if (EPI == EPI_SWIGLU) v = silu(v) * acc_up[i][j];
+      store_elem<Elem>(C + (size_t)row * n_out + n, v);
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// gfx950 MFMA kernel, bf16 in / fp32 accumulate / bf16 out
+// ------------------------------------------------------------------------------------------
+constexpr int BM = 256, BN = 256, BK = 64;
+constexpr int kStageBytes = (BM + BN) * BK * 2;   // 64 KiB
+constexpr int kStages = 2;
+constexpr int kLdsBytes = kStages * kStageBytes;  // 128 KiB of the CU's 160 KiB
+constexpr int kRowBytes = BK * 2;                 // 128 B: 8 chunks of 16 B
+
+struct MfmaArgs {
+  const uint16_t* A;    // [P, K]
+  const uint16_t* W;    // [S, w_rows, K]
+  uint16_t* C;          // [P, n_out]
+  long long P;
+  int K;
+  int w_rows;           // weight rows per slot
+  int n_out;            // output columns
+  int up_row0;          // SwiGLU: first row of the up projection inside a slot's W
+  int n_tiles;          // column tiles per row tile
+  TileTable t;
+};
+
+template <int SWZ>
+__device__ __forceinline__ int swz(int row) { return (row >> SWZ) & 7; }
+
+template <int EPI, int SWZ>
+__global__ __launch_bounds__(256, 1) void gemm_mfma_kernel(MfmaArgs a) {
+  extern __shared__ __attribute__((aligned(1024))) char smem[];
+  constexpr int BN_OUT = EPI == EPI_SWIGLU ? BN / 2 : BN;
+
+  // ---- which tile: workgroups are dealt round-robin to the 8 XCDs, so give each XCD a
+  // contiguous run of the tile order; in that order kGroupM row tiles share a column tile.
+  const int n_row_tiles = a.t.header[0];
+  const int row_groups = (n_row_tiles + kGroupM - 1) / kGroupM;
+  const long long total = (long long)row_groups * kGroupM * a.n_tiles;
+  const long long per_xcd = (total + 7) / 8;
+  const long long within = blockIdx.x / 8;
+  if (within >= per_xcd) return;
+  const long long lin = (long long)(blockIdx.x % 8) * per_xcd + within;
+  if (lin >= total) return;
+  const int mi_in_group = int(lin % kGroupM);
+  const long long rest = lin / kGroupM;
+  const int nt = int(rest % a.n_tiles);
+  const int row_tile = int(rest / a.n_tiles) * kGroupM + mi_in_group;
+  if (row_tile >= n_row_tiles) return;
+  const int slot = a.t.slot[row_tile];
+  const int row0 = a.t.row0[row_tile];
+  const int row_end = a.t.row_end[row_tile];
+  const int n0 = nt * BN_OUT;
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+
+  // ---- buffer descriptors: out-of-range loads return zero instead of faulting
+  const __amdgpu_buffer_rsrc_t rsrcA = __builtin_amdgcn_make_buffer_rsrc(
+      (void*)a.A, 0, (int)(uint32_t)((unsigned long long)a.P * a.K * 2), 0x00020000);
+  const __amdgpu_buffer_rsrc_t rsrcB = __builtin_amdgcn_make_buffer_rsrc(
+      (void*)(a.W + (size_t)slot * a.w_rows * a.K), 0, (int)(uint32_t)((unsigned long long)a.w_rows * a.K * 2),
+      0x00020000);
+
+  // ---- per-lane global offsets of the 8 + 8 direct-to-LDS loads of one stage.
+  // Load u of a 256-row operand tile fills LDS bytes [u*1024, u*1024+1024): 8 rows of 128 B,
+  // lane l landing at row 8u + l/8, 16-byte chunk l%8.  That LDS chunk must hold logical
+  // chunk (l%8) ^ swz(row), so the lane fetches that one.
+  int voffA[8], voffB[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    const int r = (wave * 8 + i) * 8 + (lane >> 3);
+    const int chunk = (lane & 7) ^ swz<SWZ>(r);
+    int ga = row0 + r;
+    ga = ga < row_end ? ga : row_end - 1;  // rows past the slot's end repeat its last row (never stored)
+    voffA[i] = (int)(((uint32_t)ga * (uint32_t)a.K + (uint32_t)chunk * 8u) * 2u);
+    int gb;
+    if (EPI == EPI_SWIGLU) {
+      const int f = r >> 5;  // fragment index: even = gate rows, odd = up rows
+      gb = n0 + (f >> 1) * 32 + (r & 31) + ((f & 1) ? a.up_row0 : 0);
+    } else {
+      gb = n0 + r;
+    }
+    voffB[i] = (int)(((uint32_t)gb * (uint32_t)a.K + (uint32_t)chunk * 8u) * 2u);
+  }
+
+  auto issue_stage = [&](int stage, int k0) {
+    char* sA = smem + stage * kStageBytes;
+    char* sB = sA + BM * kRowBytes;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int u = wave * 8 + i;
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrcA, (__attribute__((address_space(3))) void*)(sA + u * 1024),
+                                               16, voffA[i], k0 * 2, 0, 0);
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrcB, (__attribute__((address_space(3))) void*)(sB + u * 1024),
+                                               16, voffB[i], k0 * 2, 0, 0);
+    }
+  };
+
+  // ---- fragment read addresses: lane l reads row (l%32) of a 32-row fragment, logical chunk
+  // 2*ks + l/32 of the 64-wide K slice
+  int fragoff[4];
+  {
+    const int r = lane & 31;
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) fragoff[ks] = r * kRowBytes + (((ks * 2 + (lane >> 5)) ^ swz<SWZ>(r)) << 4);
+  }
+  const int xbase = wm * 128 * kRowBytes;                   // this wave's 128 activation rows
+  const int wbase = BM * kRowBytes + wn * 128 * kRowBytes;  // this wave's 128 weight rows
+
+  f32x16 acc[4][4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+  const int k_steps = a.K / BK;
+  issue_stage(0, 0);
+  __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wave's loads have landed in LDS
+  __syncthreads();
+
+  for (int kt = 0; kt < k_steps; ++kt) {
+    const int cur = kt & 1;
+    if (kt + 1 < k_steps) issue_stage(cur ^ 1, (kt + 1) * BK);
+    const char* stage = smem + cur * kStageBytes;
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+      bf16x8 xf[4], wf[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        xf[i] = *(const bf16x8*)(stage + xbase + i * 32 * kRowBytes + fragoff[ks]);
+        wf[i] = *(const bf16x8*)(stage + wbase + i * 32 * kRowBytes + fragoff[ks]);
+      }
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[i], xf[j], acc[i][j], 0, 0, 0);
+    }
+    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): next stage's loads of this wave are in LDS
+    __syncthreads();                     // ... and everyone's; everyone is done reading `cur`
+  }
+
+  // ---- epilogue.  acc[i][j] is the 32x32 block (weight fragment i) x (activation fragment j);
+  // lane l holds activation row j*32 + l%32 and, for g = 0..3, the 4 consecutive weight
+  // rows i*32 + 8g + 4*(l/32) + 0..3  -> 4 consecutive output columns.
+  const int half = lane >> 5;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const int row = row0 + wm * 128 + j * 32 + (lane & 31);
+    if (row >= row_end) continue;
+    uint16_t* crow = a.C + (size_t)row * a.n_out;
+    if (EPI == EPI_SWIGLU) {
+#pragma unroll
+      for (int q = 0; q < 2; ++q)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const int col = n0 + wn * 64 + q * 32 + 8 * g + 4 * half;
+          uint16_t o[4];
+#pragma unroll
+          for (int r = 0; r < 4; ++r)
+            o[r] = lz::f32_to_bf16(silu(acc[2 * q][j][4 * g + r]) * acc[2 * q + 1][j][4 * g + r]);
+          uint2 pk;
+          pk.x = uint32_t(o[0]) | (uint32_t(o[1]) << 16);
+          pk.y = uint32_t(o[2]) | (uint32_t(o[3]) << 16);
+          *(uint2*)(crow + col) = pk;
+        }
+    } else {
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const int col = n0 + wn * 128 + i * 32 + 8 * g + 4 * half;
+          uint16_t o[4];
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            float v = acc[i][j][4 * g + r];
+            if (EPI == EPI_GELU) v = gelu_exact(v);
+            o[r] = lz::f32_to_bf16(v);
+          }
+          uint2 pk;
+          pk.x = uint32_t(o[0]) | (uint32_t(o[1]) << 16);
+          pk.y = uint32_t(o[2]) | (uint32_t(o[3]) << 16);
+          *(uint2*)(crow + col) = pk;
+        }
+    }
+  }
+}
+
+template <int EPI>
+int32_t launch_mfma(const MfmaArgs& a, hipStream_t st) {
+  auto kern = gemm_mfma_kernel<EPI, 0>;
+  static bool configured = false;  // per-process attribute; idempotent, so a benign race at worst
+  if (!configured) {
+    if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes) !=
+        hipSuccess)
+      return LZ_EHIP;
+    configured = true;
+  }
+  const long long total = (long long)a.t.capacity * a.n_tiles;
+  const long long per_xcd = (total + 7) / 8;
+  hipLaunchKernelGGL(kern, dim3((unsigned)(per_xcd * 8)), dim3(256), kLdsBytes, st, a);
+  return lz::launch_status();
+}
+
+inline bool mfma_shape(const lz_shape* s) {
+  if (s->dtype != LZ_BF16) return false;
+  if (s->d % BN != 0 || s->d % BK != 0 || s->ffn % BK != 0) return false;
+  return s->ffn % (s->act == LZ_SWIGLU ? BN / 2 : BN) == 0;
+}
+
+struct FfnWorkspace {
+  void* hidden;
+  void* tiles;
+  size_t total_bytes;
+  int BMrows;
+};
+
+FfnWorkspace carve_ffn(void* ws, const lz_shape* s) {
+  FfnWorkspace w;
+  const long long P = (long long)s->T * s->k;
+  w.BMrows = mfma_shape(s) ? BM : 64;
+  const size_t hidden_bytes = lz::align256((size_t)P * s->ffn * lz::elem_bytes(s->dtype));
+  w.hidden = ws;
+  w.tiles = (char*)ws + hidden_bytes;
+  w.total_bytes = hidden_bytes + tile_table_bytes(P, s->N * s->c, w.BMrows);
+  return w;
+}
+
+template <typename Elem>
+int32_t run_generic(const lz_shape* s, const void* xp, const void* w1, const void* w2, void* hidden,
+                    void* yp, const TileTable& t, hipStream_t st) {
+  const int n1 = s->ffn * (s->act == LZ_SWIGLU ? 2 : 1);
+  const dim3 g1((s->ffn + 63) / 64, t.capacity), g2((s->d + 63) / 64, t.capacity);
+  if (s->act == LZ_SWIGLU)
+    hipLaunchKernelGGL((gemm_generic_kernel<Elem, EPI_SWIGLU>), g1, dim3(256), 0, st, (const Elem*)xp, s->d,
+                       (const Elem*)w1, (size_t)n1 * s->d, s->ffn, s->ffn, (Elem*)hidden, t);
+  else
+    hipLaunchKernelGGL((gemm_generic_kernel<Elem, EPI_GELU>), g1, dim3(256), 0, st, (const Elem*)xp, s->d,
+                       (const Elem*)w1, (size_t)n1 * s->d, s->ffn, 0, (Elem*)hidden, t);
+  hipLaunchKernelGGL((gemm_generic_kernel<Elem, EPI_NONE>), g2, dim3(256), 0, st, (const Elem*)hidden, s->ffn,
+                     (const Elem*)w2, (size_t)s->d * s->ffn, s->d, 0, (Elem*)yp, t);
+  return lz::launch_status();
+}
+
+}  // namespace
+
+extern "C" size_t lz_ffn_workspace_bytes(const lz_shape* shape) {
+  if (!lz::shape_ok(shape)) return 0;
+  return carve_ffn(nullptr, shape).total_bytes;
+}
+
+extern "C" int32_t lz_expert_ffn(const void* xp, const int32_t* slot_offsets, const void* w1,
+                                 const void* w2, const lz_shape* shape, void* yp, void* ws,
+                                 size_t ws_bytes, void* stream) {
+  if (!lz::shape_ok(shape)) return LZ_ESHAPE;
+  const long long P = (long long)shape->T * shape->k;
+  if (P == 0) return LZ_OK;
+  if (!xp || !slot_offsets || !w1 || !w2 || !yp) return LZ_EINVAL;
+  const FfnWorkspace w = carve_ffn(ws, shape);
+  if (!ws || (uintptr_t)ws % 256 != 0 || ws_bytes < w.total_bytes) return LZ_EWORKSPACE;
+  hipStream_t st = (hipStream_t)stream;
+  const int S = shape->N * shape->c;
+  TileTable t = carve_tiles(w.tiles, P, S, w.BMrows);
+  hipLaunchKernelGGL(build_tiles_kernel, dim3(1), dim3(256), 0, st, slot_offsets, S, P, w.BMrows, t);
+
+  if (!mfma_shape(shape)) {
+    if (shape->dtype == LZ_F32) return run_generic<float>(shape, xp, w1, w2, w.hidden, yp, t, st);
+    return run_generic<uint16_t>(shape, xp, w1, w2, w.hidden, yp, t, st);
+  }
+
+  const bool swiglu = shape->act == LZ_SWIGLU;
+  MfmaArgs g1{};
+  g1.A = (const uint16_t*)xp;
+  g1.W = (const uint16_t*)w1;
+  g1.C = (uint16_t*)w.hidden;
+  g1.P = P;
+  g1.K = shape->d;
+  g1.w_rows = shape->ffn * (swiglu ? 2 : 1);
+  g1.n_out = shape->ffn;
+  g1.up_row0 = swiglu ? shape->ffn : 0;
+  g1.n_tiles = shape->ffn / (swiglu ? BN / 2 : BN);
+  g1.t = t;
+  int32_t rc = swiglu ? launch_mfma<EPI_SWIGLU>(g1, st) : launch_mfma<EPI_GELU>(g1, st);
+  if (rc != LZ_OK) return rc;
+
+  MfmaArgs g2{};
+  g2.A = (const uint16_t*)w.hidden;
+  g2.W = (const uint16_t*)w2;
+  g2.C = (uint16_t*)yp;
+  g2.P = P;
+  g2.K = shape->ffn;
+  g2.w_rows = shape->d;
+  g2.n_out = shape->d;
+  g2.up_row0 = 0;
+  g2.n_tiles = shape->d / BN;
+  g2.t = t;
+  return launch_mfma<EPI_NONE>(g2, st);
+}

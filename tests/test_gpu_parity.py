@@ -1,0 +1,281 @@
+"""GPU parity: every call of the C ABI against the CPU oracle on the same seeded inputs.
+
+Index work (ids, counts, offsets, row maps, permuted bytes) must match bit for bit;
+floating point within the stated tolerances: gates 2e-6 relative (fp32 exp/div vs fp64),
+outputs max|err|/max|ref| <= 1e-5 (fp32 config) or 2e-2 (bf16).
+"""
+import numpy as np
+import pytest
+
+torch = pytest.importorskip("torch")
+
+import paper_2407_04656_amd as lz
+from oracle import moe_layer as om
+from oracle import planner as op
+from workloads import CONFIGS, expert_weights, f32_to_bf16_bits, step_inputs
+from workloads.configs import scaled
+
+from gpu_util import (DEV, check_dispatch_exact, oracle_plan, rel_err, run_layer, to_dev, to_host,
+                      tolerance)
+
+pytestmark = pytest.mark.gpu
+
+GATE_RTOL = 2e-6
+
+
+def _route_gpu(logits, k):
+    T, E = logits.shape
+    ids = torch.empty((T, k), dtype=torch.int32, device=DEV)
+    gates = torch.empty((T, k), dtype=torch.float32, device=DEV)
+    lz.lz_route(to_dev(logits), T, E, k, ids, gates)
+    torch.cuda.synchronize()
+    return to_host(ids), to_host(gates)
+
+
+@pytest.mark.parametrize("T,E,k", [(1, 1, 1), (5, 2, 2), (300, 3, 1), (1000, 8, 2), (777, 12, 3),
+                                   (513, 32, 2), (2050, 64, 6), (130, 100, 8), (64, 256, 8), (33, 7, 7)])
+@pytest.mark.parametrize("ties", [False, True])
+def test_route(T, E, k, ties):
+    rng = np.random.default_rng(100 + T + E + k)
+    z = rng.standard_normal((T, E)).astype(np.float32)
+    if ties:
+        z = (np.round(z * 2) / 2).astype(np.float32)
+        z[0, :] = -0.0
+        z[0, ::2] = 0.0
+    ids_ref, gates_ref = om.route(z, k)
+    ids, gates = _route_gpu(z, k)
+    assert np.array_equal(ids, ids_ref)
+    assert np.allclose(gates, gates_ref, rtol=GATE_RTOL, atol=0)
+    assert np.allclose(gates.sum(axis=1), 1.0, atol=1e-6)
+
+
+def test_route_workload_logits():
+    for name in ("c1_tiny", "c4_finegrained"):
+        cfg = CONFIGS[name]
+        z = step_inputs(cfg, with_x=False)["logits"]
+        ids_ref, gates_ref = om.route(z, cfg.k)
+        ids, gates = _route_gpu(z, cfg.k)
+        assert np.array_equal(ids, ids_ref)
+        assert np.allclose(gates, gates_ref, rtol=GATE_RTOL, atol=0)
+
+
+def _plan_gpu(ids, shape, off, plan):
+    s = shape
+    i32 = torch.int32
+    out = {
+        "slot_counts": torch.full((s.S,), -7, dtype=i32, device=DEV),
+        "slot_offsets": torch.full((s.S + 1,), -7, dtype=i32, device=DEV),
+        "pair_to_row": torch.full((max(s.P, 1),), -7, dtype=i32, device=DEV),
+        "row_to_pair": torch.full((max(s.P, 1),), -7, dtype=i32, device=DEV),
+        "Tej": torch.full((s.E, s.N), -7, dtype=i32, device=DEV),
+        "D": torch.full((s.E, s.N, s.N), -7, dtype=i32, device=DEV),
+        "status": torch.full((1,), -7, dtype=i32, device=DEV),
+    }
+    nbytes = lz.lz_plan_workspace_bytes(s)
+    ws = torch.empty(nbytes, dtype=torch.uint8, device=DEV)
+    lz.lz_plan_dispatch(to_dev(ids) if s.P else None, s, to_dev(np.asarray(off, dtype=np.int32)),
+                        to_dev(np.asarray(plan, dtype=np.int32)), out["slot_counts"], out["slot_offsets"],
+                        out["pair_to_row"] if s.P else None, out["row_to_pair"] if s.P else None,
+                        out["Tej"], out["D"], out["status"], ws, nbytes)
+    torch.cuda.synchronize()
+    return {k: to_host(v) for k, v in out.items()}
+
+
+def _random_plan(rng, E, N, c):
+    plan = rng.integers(0, E, size=N * c)
+    plan[rng.permutation(N * c)[:E]] = np.arange(E)
+    return plan.astype(np.int32)
+
+
+@pytest.mark.parametrize("T,E,k,N,c", [
+    (256, 8, 2, 4, 4), (1000, 8, 2, 8, 2), (4099, 32, 2, 8, 6), (3001, 64, 6, 16, 8),
+    (700, 5, 1, 3, 2), (513, 16, 4, 1, 16), (2049, 12, 3, 6, 8), (50, 4, 2, 7, 1), (1, 3, 1, 2, 2)])
+def test_plan_dispatch_random_plans(T, E, k, N, c):
+    rng = np.random.default_rng(T * 31 + E)
+    shape = lz.Shape(T, 64, 64, E, k, N, c, lz.LZ_BF16, lz.LZ_GELU)
+    bias = -1.2 * np.log(rng.permutation(E) + 1.0)
+    z = (rng.standard_normal((T, E)) + bias).astype(np.float32)
+    ids, _ = om.route(z, k)
+    cuts = np.sort(rng.integers(0, T + 1, size=N - 1)) if N > 1 else np.array([], dtype=np.int64)
+    for off in (np.array([(i * T) // N for i in range(N + 1)]), np.concatenate([[0], cuts, [T]])):
+        for plan in (_random_plan(rng, E, N, c), _random_plan(rng, E, N, c)):
+            ref = om.plan_dispatch(ids, off, plan, E, N, c)
+            got = _plan_gpu(ids, shape, off, plan)
+            assert got["status"][0] == 0
+            for key in ("Tej", "D", "slot_counts", "slot_offsets", "pair_to_row", "row_to_pair"):
+                assert np.array_equal(got[key], ref[key]), key
+
+
+def test_plan_dispatch_is_deterministic_and_flags_bad_input():
+    rng = np.random.default_rng(5)
+    T, E, k, N, c = 3000, 16, 2, 4, 4
+    shape = lz.Shape(T, 64, 64, E, k, N, c, lz.LZ_BF16, lz.LZ_GELU)
+    ids, _ = om.route(rng.standard_normal((T, E)).astype(np.float32), k)
+    off = np.array([0, 750, 1500, 2250, 3000])
+    plan = _random_plan(rng, E, N, c)
+    a = _plan_gpu(ids, shape, off, plan)
+    b = _plan_gpu(ids, shape, off, plan)
+    for key in a:
+        assert np.array_equal(a[key], b[key])
+    # an expert with tokens but no replica: flagged, its pairs get no row, nothing else moves
+    plan2 = plan.copy()
+    victim = int(ids[0, 0])
+    plan2[plan2 == victim] = (victim + 1) % E
+    got = _plan_gpu(ids, shape, off, plan2)
+    assert got["status"][0] & 1
+    lost = ids.reshape(-1) == victim
+    assert np.all(got["pair_to_row"][lost] == -1) and np.all(got["pair_to_row"][~lost] >= 0)
+    assert got["slot_offsets"][-1] == T * k - lost.sum()
+    placed = got["row_to_pair"][:got["slot_offsets"][-1]]
+    assert np.array_equal(np.sort(placed), np.nonzero(~lost)[0])
+    # ids out of range and a broken rank split are flagged and stay in bounds
+    ids_bad = ids.copy()
+    ids_bad[5, 1] = E + 3
+    ids_bad[9, 0] = -2
+    got = _plan_gpu(ids_bad, shape, np.array([0, 900, 800, 5000, 3000]), plan)
+    assert got["status"][0] & 2 and got["status"][0] & 4
+    assert got["pair_to_row"][5 * k + 1] == -1 and got["pair_to_row"][9 * k] == -1
+    assert got["pair_to_row"].max() < T * k
+
+
+def test_plan_dispatch_empty_batch():
+    shape = lz.Shape(0, 64, 64, 4, 2, 2, 2, lz.LZ_BF16, lz.LZ_GELU)
+    got = _plan_gpu(np.zeros((0, 2), dtype=np.int32), shape, np.array([0, 0, 0]), np.array([0, 1, 2, 3]))
+    assert np.all(got["slot_counts"] == 0) and np.all(got["slot_offsets"] == 0) and got["status"][0] == 0
+
+
+@pytest.mark.parametrize("dtype,d", [("bf16", 4096), ("bf16", 72), ("f32", 128), ("f32", 33), ("bf16", 7)])
+def test_permute_and_combine(dtype, d):
+    rng = np.random.default_rng(d)
+    T, k, E, N, c = 777, 3, 8, 4, 3
+    bf16 = dtype == "bf16"
+    shape = lz.Shape(T, d, 64, E, k, N, c, lz.LZ_BF16 if bf16 else lz.LZ_F32, lz.LZ_GELU)
+    x = rng.standard_normal((T, d)).astype(np.float32)
+    xh = f32_to_bf16_bits(x) if bf16 else x
+    z = rng.standard_normal((T, E)).astype(np.float32)
+    ids, gates = om.route(z, k)
+    ref = om.plan_dispatch(ids, np.array([(i * T) // N for i in range(N + 1)]), _random_plan(rng, E, N, c), E, N, c)
+    tdt = torch.bfloat16 if bf16 else torch.float32
+    xp = torch.empty((T * k, d), dtype=tdt, device=DEV)
+    lz.lz_permute(to_dev(xh, bf16), to_dev(ref["row_to_pair"]), shape, xp)
+    torch.cuda.synchronize()
+    assert np.array_equal(to_host(xp), om.permute(xh, ref["row_to_pair"], k))      # a copy: bit exact
+    y = torch.empty((T, d), dtype=tdt, device=DEV)
+    g32 = gates.astype(np.float32)
+    lz.lz_unpermute_combine(xp, to_dev(ref["pair_to_row"]), to_dev(g32), shape, y)
+    torch.cuda.synchronize()
+    y_ref = om.unpermute_combine(om.permute(xh, ref["row_to_pair"], k), ref["pair_to_row"], g32)
+    assert rel_err(to_host(y), y_ref) <= (2e-2 if bf16 else 1e-5)
+    # identity experts: the combine returns x scaled by the sum of its gates (= x)
+    assert rel_err(to_host(y), om.widen(xh)) <= (2e-2 if bf16 else 1e-5)
+    # rows / pairs outside the map are zero-filled / skipped
+    r2p = ref["row_to_pair"].copy()
+    r2p[3] = -1
+    r2p[4] = T * k + 5
+    lz.lz_permute(to_dev(xh, bf16), to_dev(r2p), shape, xp)
+    torch.cuda.synchronize()
+    got = to_host(xp)
+    assert not got[3].any() and not got[4].any() and np.array_equal(got[5], xh[r2p[5] // k])
+
+
+def _ffn_case(cfg, counts, seed):
+    """expert_ffn on a hand-made slot layout (ragged, empty and one-row slots)."""
+    rng = np.random.default_rng(seed)
+    S = cfg.N * cfg.c
+    counts = np.asarray(counts)
+    assert len(counts) == S and counts.sum() == cfg.T * cfg.k
+    offsets = np.zeros(S + 1, dtype=np.int32)
+    offsets[1:] = np.cumsum(counts)
+    slot_expert = rng.integers(0, cfg.E, size=S).astype(np.int32)
+    w = expert_weights(cfg, threads=4)
+    bf16 = cfg.dtype == "bf16"
+    xp = rng.standard_normal((cfg.T * cfg.k, cfg.d)).astype(np.float32)
+    xph = f32_to_bf16_bits(xp) if bf16 else xp
+    shape = lz.Shape.from_config(cfg)
+    tdt = torch.bfloat16 if bf16 else torch.float32
+    w1 = to_dev(w["w1"][slot_expert], bf16)
+    w2 = to_dev(w["w2"][slot_expert], bf16)
+    yp = torch.zeros((cfg.T * cfg.k, cfg.d), dtype=tdt, device=DEV)
+    nbytes = lz.lz_ffn_workspace_bytes(shape)
+    ws = torch.empty(nbytes, dtype=torch.uint8, device=DEV)
+    lz.lz_expert_ffn(to_dev(xph, bf16), to_dev(offsets), w1, w2, shape, yp, ws, nbytes)
+    torch.cuda.synchronize()
+    ref = om.expert_ffn_rows(xph, offsets, slot_expert, w["w1"], w["w2"], cfg.act)
+    return rel_err(to_host(yp), ref)
+
+
+@pytest.mark.parametrize("act", ["gelu", "swiglu"])
+def test_expert_ffn_fp32_generic(act):
+    cfg = scaled(CONFIGS["c1_tiny"], act=act, T=150, k=2, d=72, ffn=100, N=3, c=2)
+    assert _ffn_case(cfg, [70, 0, 1, 129, 65, 35], 1) <= 1e-5
+
+
+@pytest.mark.parametrize("act", ["gelu", "swiglu"])
+def test_expert_ffn_bf16_generic_odd_shape(act):
+    cfg = scaled(CONFIGS["c1_tiny"], act=act, dtype="bf16", T=150, k=2, d=72, ffn=104, N=3, c=2)
+    assert _ffn_case(cfg, [70, 0, 1, 129, 65, 35], 2) <= 2e-2
+
+
+@pytest.mark.parametrize("act,d,ffn", [("gelu", 256, 256), ("swiglu", 256, 128), ("swiglu", 512, 384),
+                                       ("gelu", 512, 512)])
+def test_expert_ffn_bf16_mfma_ragged(act, d, ffn):
+    cfg = scaled(CONFIGS["c1_tiny"], act=act, dtype="bf16", T=700, k=2, d=d, ffn=ffn, N=4, c=2)
+    # several row tiles, a tile boundary +1, an empty slot, a one-row slot, a ragged tail
+    assert _ffn_case(cfg, [257, 0, 1, 512, 300, 255, 74, 1], 3) <= 2e-2
+
+
+def test_expert_ffn_clips_bad_offsets():
+    cfg = scaled(CONFIGS["c1_tiny"], dtype="bf16", act="swiglu", T=256, k=2, d=256, ffn=128, N=2, c=2)
+    shape = lz.Shape.from_config(cfg)
+    nbytes = lz.lz_ffn_workspace_bytes(shape)
+    ws = torch.empty(nbytes, dtype=torch.uint8, device=DEV)
+    xp = torch.zeros((512, 256), dtype=torch.bfloat16, device=DEV)
+    w1 = torch.zeros((4, 256, 256), dtype=torch.bfloat16, device=DEV)
+    w2 = torch.zeros((4, 256, 128), dtype=torch.bfloat16, device=DEV)
+    yp = torch.ones((512, 256), dtype=torch.bfloat16, device=DEV)
+    bad = to_dev(np.array([-50, 100, 90, 100000, 7], dtype=np.int32))
+    lz.lz_expert_ffn(xp, bad, w1, w2, shape, yp, ws, nbytes)
+    torch.cuda.synchronize()
+    assert torch.isfinite(yp.float()).all()
+    with pytest.raises(lz.LzError):
+        lz.lz_expert_ffn(xp, bad, w1, w2, shape, yp, ws, nbytes - 256)
+
+
+def test_layer_c1_full():
+    """Config 1 in full: dispatch bit-exact, output within 1e-5 of the fp64 definition."""
+    cfg = CONFIGS["c1_tiny"]
+    inp = step_inputs(cfg)
+    w = expert_weights(cfg, threads=4)
+    ids_ref, gates_ref = om.route(inp["logits"], cfg.k)
+    plan = oracle_plan(cfg, ids_ref)
+    assert plan.reshape(4, 4).tolist() == [[0, 1, 3, 5], [0, 1, 3, 5], [0, 2, 4, 6], [1, 2, 4, 7]]
+    layer = run_layer(cfg, plan, inp, w)
+    ref = om.plan_dispatch(ids_ref, inp["rank_tok_off"], plan, cfg.E, cfg.N, cfg.c)
+    check_dispatch_exact(cfg, layer, ids_ref, ref)
+    assert np.allclose(to_host(layer.topk_gates), gates_ref, rtol=GATE_RTOL, atol=0)
+    assert np.array_equal(to_host(layer.xp), om.permute(inp["x"], ref["row_to_pair"], cfg.k))
+    y_ref = om.layer_output(inp["x"], ids_ref, gates_ref, w["w1"], w["w2"], cfg.act)
+    assert rel_err(to_host(layer.y), y_ref) <= tolerance(cfg)
+    # intermediate buffer against the oracle's per-slot FFN
+    yp_ref = om.expert_ffn_rows(to_host(layer.xp), ref["slot_offsets"], plan, w["w1"], w["w2"], cfg.act)
+    assert rel_err(to_host(layer.yp), yp_ref) <= tolerance(cfg)
+
+
+@pytest.mark.parametrize("name,T,d,ffn", [("c2_mixtral", 1500, 512, 640), ("c3_gptmoe", 2100, 256, 512),
+                                          ("c4_finegrained", 900, 256, 384)])
+def test_layer_reduced_configs(name, T, d, ffn):
+    """The bf16 configs at a size the oracle evaluates in full (several tiles, ragged tails)."""
+    cfg = scaled(CONFIGS[name], T=T, d=d, ffn=ffn)
+    inp = step_inputs(cfg)
+    w = expert_weights(cfg, threads=4)
+    ids_ref, gates_ref = om.route(inp["logits"], cfg.k)
+    plan = oracle_plan(cfg, ids_ref)
+    t_e = np.bincount(ids_ref.reshape(-1), minlength=cfg.E)
+    r = lz.lz_allocate_replicas(t_e, cfg.N, cfg.c, cfg.f)
+    assert np.array_equal(lz.lz_place_mro(r, t_e, cfg.N, cfg.c), plan)
+    layer = run_layer(cfg, plan, inp, w)
+    ref = om.plan_dispatch(ids_ref, inp["rank_tok_off"], plan, cfg.E, cfg.N, cfg.c)
+    check_dispatch_exact(cfg, layer, ids_ref, ref)
+    assert np.array_equal(to_host(layer.xp), om.permute(inp["x"], ref["row_to_pair"], cfg.k))
+    y_ref = om.layer_output(inp["x"], ids_ref, gates_ref, w["w1"], w["w2"], cfg.act)
+    assert rel_err(to_host(layer.y), y_ref) <= tolerance(cfg)
