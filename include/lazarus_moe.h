@@ -141,6 +141,18 @@ int32_t lz_expert_ffn(const void* xp, const int32_t* slot_offsets,
                       const void* w1, const void* w2, const lz_shape* shape,
                       void* yp, void* ws, size_t ws_bytes, void* stream);
 
+/* The three stages of lz_expert_ffn as separate calls, for callers that want to time or
+ * interleave them; lz_expert_ffn is exactly tiles -> up -> down on the same workspace.
+ *   lz_ffn_tiles  turns slot_offsets into the row-tile table kept in ws
+ *   lz_ffn_up     hidden = act(xp W1^T) per slot, hidden kept in ws        (needs tiles)
+ *   lz_ffn_down   yp = hidden W2^T per slot                                (needs up)    */
+int32_t lz_ffn_tiles(const int32_t* slot_offsets, const lz_shape* shape, void* ws, size_t ws_bytes,
+                     void* stream);
+int32_t lz_ffn_up(const void* xp, const void* w1, const lz_shape* shape, void* ws, size_t ws_bytes,
+                  void* stream);
+int32_t lz_ffn_down(const void* w2, const lz_shape* shape, void* yp, void* ws, size_t ws_bytes,
+                    void* stream);
+
 /* Inverse permutation and gate-weighted combine (Sec. 2.1, the second all-to-all and the
  * combine): y[t,:] = sum_{kk<k} topk_gates[t,kk] * yp[pair_to_row[t*k+kk], :], summed in
  * fp32 in ascending kk and rounded once; a pair whose row is outside [0,P) contributes 0.

@@ -11,7 +11,7 @@ __all__ = [
     "LZ_F32", "LZ_BF16", "LZ_GELU", "LZ_SWIGLU", "LzError", "Shape", "lib", "lib_path",
     "lz_strerror", "lz_version", "lz_plan_workspace_bytes", "lz_ffn_workspace_bytes",
     "lz_route", "lz_plan_dispatch", "lz_permute", "lz_expert_ffn", "lz_unpermute_combine",
-    "lz_allocate_replicas", "lz_place_mro", "lz_place_spread", "lz_recovery_probability",
+    "lz_ffn_tiles", "lz_ffn_up", "lz_ffn_down", "lz_allocate_replicas", "lz_place_mro", "lz_place_spread", "lz_recovery_probability",
     "lz_replan", "lz_apply_transfers", "MoELayer",
 ]
 
@@ -87,6 +87,9 @@ def _load():
         "lz_permute": (i32, [vp, vp, sp, vp, vp]),
         "lz_expert_ffn": (i32, [vp, vp, vp, vp, sp, vp, vp, u64, vp]),
         "lz_unpermute_combine": (i32, [vp, vp, vp, sp, vp, vp]),
+        "lz_ffn_tiles": (i32, [vp, sp, vp, u64, vp]),
+        "lz_ffn_up": (i32, [vp, vp, sp, vp, u64, vp]),
+        "lz_ffn_down": (i32, [vp, sp, vp, vp, u64, vp]),
         "lz_allocate_replicas": (i32, [vp, i32, i32, i32, i32, vp]),
         "lz_place_mro": (i32, [vp, vp, i32, i32, i32, vp]),
         "lz_place_spread": (i32, [vp, i32, i32, i32, vp]),
@@ -101,12 +104,6 @@ def _load():
 
 
 lib = _load()
-EXPORTS = ["lz_strerror", "lz_version", "lz_plan_workspace_bytes", "lz_ffn_workspace_bytes", "lz_route",
-           "lz_plan_dispatch", "lz_permute", "lz_expert_ffn", "lz_unpermute_combine",
-           "lz_allocate_replicas", "lz_place_mro", "lz_place_spread", "lz_recovery_probability",
-           "lz_replan", "lz_apply_transfers"]
-
-
 def lz_strerror(code: int) -> str:
     return lib.lz_strerror(int(code)).decode()
 
@@ -168,6 +165,21 @@ def lz_expert_ffn(xp, slot_offsets, w1, w2, shape, yp, ws, ws_bytes, stream=None
     _check(lib.lz_expert_ffn(_ptr(xp), _ptr(slot_offsets), _ptr(w1), _ptr(w2), C.byref(shape.c_struct()),
                              _ptr(yp), _ptr(ws), ws_bytes,
                              _stream() if stream is None else stream), "lz_expert_ffn")
+
+
+def lz_ffn_tiles(slot_offsets, shape, ws, ws_bytes, stream=None):
+    _check(lib.lz_ffn_tiles(_ptr(slot_offsets), C.byref(shape.c_struct()), _ptr(ws), ws_bytes,
+                            _stream() if stream is None else stream), "lz_ffn_tiles")
+
+
+def lz_ffn_up(xp, w1, shape, ws, ws_bytes, stream=None):
+    _check(lib.lz_ffn_up(_ptr(xp), _ptr(w1), C.byref(shape.c_struct()), _ptr(ws), ws_bytes,
+                         _stream() if stream is None else stream), "lz_ffn_up")
+
+
+def lz_ffn_down(w2, shape, yp, ws, ws_bytes, stream=None):
+    _check(lib.lz_ffn_down(_ptr(w2), C.byref(shape.c_struct()), _ptr(yp), _ptr(ws), ws_bytes,
+                           _stream() if stream is None else stream), "lz_ffn_down")
 
 
 def lz_unpermute_combine(yp, pair_to_row, topk_gates, shape, y, stream=None):

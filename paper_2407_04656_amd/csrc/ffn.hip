@@ -401,22 +401,6 @@ FfnWorkspace carve_ffn(void* ws, const lz_shape* s) {
   return w;
 }
 
-template <typename Elem>
-int32_t run_generic(const lz_shape* s, const void* xp, const void* w1, const void* w2, void* hidden,
-                    void* yp, const TileTable& t, hipStream_t st) {
-  const int n1 = s->ffn * (s->act == LZ_SWIGLU ? 2 : 1);
-  const dim3 g1((s->ffn + 63) / 64, t.capacity), g2((s->d + 63) / 64, t.capacity);
-  if (s->act == LZ_SWIGLU)
-    hipLaunchKernelGGL((gemm_generic_kernel<Elem, EPI_SWIGLU>), g1, dim3(256), 0, st, (const Elem*)xp, s->d,
-                       (const Elem*)w1, (size_t)n1 * s->d, s->ffn, s->ffn, (Elem*)hidden, t);
-  else
-    hipLaunchKernelGGL((gemm_generic_kernel<Elem, EPI_GELU>), g1, dim3(256), 0, st, (const Elem*)xp, s->d,
-                       (const Elem*)w1, (size_t)n1 * s->d, s->ffn, 0, (Elem*)hidden, t);
-  hipLaunchKernelGGL((gemm_generic_kernel<Elem, EPI_NONE>), g2, dim3(256), 0, st, (const Elem*)hidden, s->ffn,
-                     (const Elem*)w2, (size_t)s->d * s->ffn, s->d, 0, (Elem*)yp, t);
-  return lz::launch_status();
-}
-
 }  // namespace
 
 extern "C" size_t lz_ffn_workspace_bytes(const lz_shape* shape) {
@@ -424,40 +408,103 @@ extern "C" size_t lz_ffn_workspace_bytes(const lz_shape* shape) {
   return carve_ffn(nullptr, shape).total_bytes;
 }
 
-extern "C" int32_t lz_expert_ffn(const void* xp, const int32_t* slot_offsets, const void* w1,
-                                 const void* w2, const lz_shape* shape, void* yp, void* ws,
-                                 size_t ws_bytes, void* stream) {
+namespace {
+
+int32_t check_ffn(const lz_shape* shape, void* ws, size_t ws_bytes, FfnWorkspace* w) {
   if (!lz::shape_ok(shape)) return LZ_ESHAPE;
+  *w = carve_ffn(ws, shape);
+  if (!ws || (uintptr_t)ws % 256 != 0 || ws_bytes < w->total_bytes) return LZ_EWORKSPACE;
+  return LZ_OK;
+}
+
+}  // namespace
+
+extern "C" int32_t lz_ffn_tiles(const int32_t* slot_offsets, const lz_shape* shape, void* ws,
+                                size_t ws_bytes, void* stream) {
+  FfnWorkspace w;
+  const int32_t rc = check_ffn(shape, ws, ws_bytes, &w);
+  if (rc != LZ_OK) return rc;
   const long long P = (long long)shape->T * shape->k;
   if (P == 0) return LZ_OK;
-  if (!xp || !slot_offsets || !w1 || !w2 || !yp) return LZ_EINVAL;
-  const FfnWorkspace w = carve_ffn(ws, shape);
-  if (!ws || (uintptr_t)ws % 256 != 0 || ws_bytes < w.total_bytes) return LZ_EWORKSPACE;
-  hipStream_t st = (hipStream_t)stream;
+  if (!slot_offsets) return LZ_EINVAL;
   const int S = shape->N * shape->c;
   TileTable t = carve_tiles(w.tiles, P, S, w.BMrows);
-  hipLaunchKernelGGL(build_tiles_kernel, dim3(1), dim3(256), 0, st, slot_offsets, S, P, w.BMrows, t);
+  hipLaunchKernelGGL(build_tiles_kernel, dim3(1), dim3(256), 0, (hipStream_t)stream, slot_offsets, S, P,
+                     w.BMrows, t);
+  return lz::launch_status();
+}
 
-  if (!mfma_shape(shape)) {
-    if (shape->dtype == LZ_F32) return run_generic<float>(shape, xp, w1, w2, w.hidden, yp, t, st);
-    return run_generic<uint16_t>(shape, xp, w1, w2, w.hidden, yp, t, st);
-  }
-
+extern "C" int32_t lz_ffn_up(const void* xp, const void* w1, const lz_shape* shape, void* ws,
+                             size_t ws_bytes, void* stream) {
+  FfnWorkspace w;
+  const int32_t rc = check_ffn(shape, ws, ws_bytes, &w);
+  if (rc != LZ_OK) return rc;
+  const long long P = (long long)shape->T * shape->k;
+  if (P == 0) return LZ_OK;
+  if (!xp || !w1) return LZ_EINVAL;
+  hipStream_t st = (hipStream_t)stream;
+  TileTable t = carve_tiles(w.tiles, P, shape->N * shape->c, w.BMrows);
   const bool swiglu = shape->act == LZ_SWIGLU;
+  const int n1 = shape->ffn * (swiglu ? 2 : 1);
+  if (!mfma_shape(shape)) {
+    const dim3 grid((shape->ffn + 63) / 64, t.capacity);
+    if (shape->dtype == LZ_F32) {
+      if (swiglu)
+        hipLaunchKernelGGL((gemm_generic_kernel<float, EPI_SWIGLU>), grid, dim3(256), 0, st, (const float*)xp,
+                           shape->d, (const float*)w1, (size_t)n1 * shape->d, shape->ffn, shape->ffn,
+                           (float*)w.hidden, t);
+      else
+        hipLaunchKernelGGL((gemm_generic_kernel<float, EPI_GELU>), grid, dim3(256), 0, st, (const float*)xp,
+                           shape->d, (const float*)w1, (size_t)n1 * shape->d, shape->ffn, 0,
+                           (float*)w.hidden, t);
+    } else {
+      if (swiglu)
+        hipLaunchKernelGGL((gemm_generic_kernel<uint16_t, EPI_SWIGLU>), grid, dim3(256), 0, st,
+                           (const uint16_t*)xp, shape->d, (const uint16_t*)w1, (size_t)n1 * shape->d,
+                           shape->ffn, shape->ffn, (uint16_t*)w.hidden, t);
+      else
+        hipLaunchKernelGGL((gemm_generic_kernel<uint16_t, EPI_GELU>), grid, dim3(256), 0, st,
+                           (const uint16_t*)xp, shape->d, (const uint16_t*)w1, (size_t)n1 * shape->d,
+                           shape->ffn, 0, (uint16_t*)w.hidden, t);
+    }
+    return lz::launch_status();
+  }
   MfmaArgs g1{};
   g1.A = (const uint16_t*)xp;
   g1.W = (const uint16_t*)w1;
   g1.C = (uint16_t*)w.hidden;
   g1.P = P;
   g1.K = shape->d;
-  g1.w_rows = shape->ffn * (swiglu ? 2 : 1);
+  g1.w_rows = n1;
   g1.n_out = shape->ffn;
   g1.up_row0 = swiglu ? shape->ffn : 0;
   g1.n_tiles = shape->ffn / (swiglu ? BN / 2 : BN);
   g1.t = t;
-  int32_t rc = swiglu ? launch_mfma<EPI_SWIGLU>(g1, st) : launch_mfma<EPI_GELU>(g1, st);
-  if (rc != LZ_OK) return rc;
+  return swiglu ? launch_mfma<EPI_SWIGLU>(g1, st) : launch_mfma<EPI_GELU>(g1, st);
+}
 
+extern "C" int32_t lz_ffn_down(const void* w2, const lz_shape* shape, void* yp, void* ws,
+                               size_t ws_bytes, void* stream) {
+  FfnWorkspace w;
+  const int32_t rc = check_ffn(shape, ws, ws_bytes, &w);
+  if (rc != LZ_OK) return rc;
+  const long long P = (long long)shape->T * shape->k;
+  if (P == 0) return LZ_OK;
+  if (!w2 || !yp) return LZ_EINVAL;
+  hipStream_t st = (hipStream_t)stream;
+  TileTable t = carve_tiles(w.tiles, P, shape->N * shape->c, w.BMrows);
+  if (!mfma_shape(shape)) {
+    const dim3 grid((shape->d + 63) / 64, t.capacity);
+    if (shape->dtype == LZ_F32)
+      hipLaunchKernelGGL((gemm_generic_kernel<float, EPI_NONE>), grid, dim3(256), 0, st,
+                         (const float*)w.hidden, shape->ffn, (const float*)w2,
+                         (size_t)shape->d * shape->ffn, shape->d, 0, (float*)yp, t);
+    else
+      hipLaunchKernelGGL((gemm_generic_kernel<uint16_t, EPI_NONE>), grid, dim3(256), 0, st,
+                         (const uint16_t*)w.hidden, shape->ffn, (const uint16_t*)w2,
+                         (size_t)shape->d * shape->ffn, shape->d, 0, (uint16_t*)yp, t);
+    return lz::launch_status();
+  }
   MfmaArgs g2{};
   g2.A = (const uint16_t*)w.hidden;
   g2.W = (const uint16_t*)w2;
@@ -470,4 +517,17 @@ extern "C" int32_t lz_expert_ffn(const void* xp, const int32_t* slot_offsets, co
   g2.n_tiles = shape->d / BN;
   g2.t = t;
   return launch_mfma<EPI_NONE>(g2, st);
+}
+
+extern "C" int32_t lz_expert_ffn(const void* xp, const int32_t* slot_offsets, const void* w1,
+                                 const void* w2, const lz_shape* shape, void* yp, void* ws,
+                                 size_t ws_bytes, void* stream) {
+  int32_t rc = lz_ffn_tiles(slot_offsets, shape, ws, ws_bytes, stream);
+  if (rc != LZ_OK) return rc;
+  const long long P = (long long)shape->T * shape->k;
+  if (P == 0) return LZ_OK;
+  if (!xp || !w1 || !w2 || !yp) return LZ_EINVAL;
+  rc = lz_ffn_up(xp, w1, shape, ws, ws_bytes, stream);
+  if (rc != LZ_OK) return rc;
+  return lz_ffn_down(w2, shape, yp, ws, ws_bytes, stream);
 }

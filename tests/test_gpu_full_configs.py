@@ -1,0 +1,121 @@
+"""Full-size parity for the BASELINE configs (2-5), in the launch configuration bench.py
+times: routing and dispatch bit-exact on ALL pairs; outputs on a seeded sample of tokens
+plus every token of the smallest and the largest slot, against the fp64 plain definition."""
+import numpy as np
+import pytest
+
+torch = pytest.importorskip("torch")
+
+import paper_2407_04656_amd as lz
+from oracle import moe_layer as om
+from oracle import planner as op
+from workloads import CONFIGS, expert_weights, step_inputs
+
+from dispatch_checks import check_row_maps, check_schedule_invariants
+from gpu_util import DEV, check_dispatch_exact, oracle_plan, rel_err, run_layer, to_dev, to_host, tolerance
+
+pytestmark = pytest.mark.gpu
+
+GATE_RTOL = 2e-6
+
+
+def _sample_tokens(cfg, ref, n_random, seed, cap_per_slot=192):
+    rng = np.random.default_rng(seed)
+    toks = set(rng.choice(cfg.T, size=min(n_random, cfg.T), replace=False).tolist())
+    counts = ref["slot_counts"]
+    nz = np.nonzero(counts)[0]
+    for s in (nz[np.argmin(counts[nz])], int(np.argmax(counts))):
+        rows = np.arange(ref["slot_offsets"][s], ref["slot_offsets"][s + 1])
+        if len(rows) > cap_per_slot:          # first, last and a spread of the slot's rows
+            rows = np.unique(np.concatenate([rows[:32], rows[-32:], rows[::max(1, len(rows) // 128)]]))
+        toks.update((ref["row_to_pair"][rows] // cfg.k).tolist())
+    return np.array(sorted(toks))
+
+
+def _check_outputs(cfg, layer, inp, w, ids, gates, ref, n_random, seed):
+    toks = _sample_tokens(cfg, ref, n_random, seed)
+    y_ref = om.layer_output(inp["x"], ids, gates, w["w1"], w["w2"], cfg.act, tokens=toks)
+    y = to_host(layer.y)[toks]
+    err = rel_err(y, y_ref)
+    assert err <= tolerance(cfg), err
+    # per-row normalised error as well
+    row_err = np.max(np.abs(om.widen(y) - y_ref), axis=1) / np.max(np.abs(y_ref), axis=1)
+    assert row_err.max() <= 2 * tolerance(cfg), row_err.max()
+    return err
+
+
+@pytest.mark.parametrize("name,n_random", [("c2_mixtral", 160), ("c3_gptmoe", 320), ("c4_finegrained", 256)])
+def test_full_config(name, n_random):
+    cfg = CONFIGS[name]
+    w = expert_weights(cfg, threads=16)
+    layer = None
+    plan = None
+    steps = [0] if cfg.steps == 1 else [0, cfg.reshuffle_every]   # second step: reshuffled popularity, stale plan
+    for step in steps:
+        inp = step_inputs(cfg, step)
+        ids, gates = om.route(inp["logits"], cfg.k)
+        if plan is None:
+            plan = oracle_plan(cfg, ids)
+            t_e = np.bincount(ids.reshape(-1), minlength=cfg.E)
+            r = lz.lz_allocate_replicas(t_e, cfg.N, cfg.c, cfg.f)
+            assert np.array_equal(lz.lz_place_mro(r, t_e, cfg.N, cfg.c), plan)
+        layer = run_layer(cfg, plan, inp, w, layer)
+        ref = om.plan_dispatch(ids, inp["rank_tok_off"], plan, cfg.E, cfg.N, cfg.c)
+        check_dispatch_exact(cfg, layer, ids, ref)
+        check_schedule_invariants(ref["Tej"], ref["R"], ref)
+        check_row_maps(ids, inp["rank_tok_off"], plan, cfg.E, cfg.N, cfg.c, ref["D"],
+                       {k: to_host(getattr(layer, k)) for k in
+                        ("slot_counts", "slot_offsets", "pair_to_row", "row_to_pair")})
+        assert np.allclose(to_host(layer.topk_gates), gates, rtol=GATE_RTOL, atol=0)
+        # the permuted buffer is a pure copy: compare sampled rows bit for bit
+        rows = np.random.default_rng(step).choice(cfg.T * cfg.k, size=2048, replace=False)
+        assert np.array_equal(to_host(layer.xp[torch.from_numpy(rows).to(DEV)]),
+                              inp["x"][ref["row_to_pair"][rows] // cfg.k])
+        _check_outputs(cfg, layer, inp, w, ids, gates, ref, n_random, seed=step)
+
+
+def test_post_failure_replan():
+    """Config 5: config 3's step-0 plan loses ranks 2 and 5; re-plan on 6 ranks x 8 slots, move the
+    weights with the transfer list, and run the layer under the new plan."""
+    cfg = CONFIGS["c5_postfailure"]
+    base = CONFIGS[cfg.base]
+    w = expert_weights(base, threads=16)            # the model's weights are those of the base config
+    inp0 = step_inputs(base, 0)
+    ids0, _ = om.route(inp0["logits"], base.k)
+    old_plan = oracle_plan(base, ids0)
+    t_e = np.bincount(ids0.reshape(-1), minlength=base.E)
+    alive = np.ones(cfg.base_N, dtype=np.uint8)
+    alive[list(cfg.drop_ranks)] = 0
+    ref_re = op.replan(old_plan.tolist(), cfg.base_N, cfg.base_c, alive, t_e, cfg.c, cfg.f)
+    got_re = lz.lz_replan(old_plan, cfg.base_N, cfg.base_c, alive, t_e, cfg.c, cfg.f)
+    assert got_re["N_new"] == cfg.N
+    assert got_re["new_slot_expert"].tolist() == ref_re["new_slot_expert"]
+    assert got_re["transfers"] == ref_re["transfers"]
+    new_plan = got_re["new_slot_expert"]
+
+    # old per-slot weights on the device, new ones filled only by the transfer list
+    shape_old = lz.Shape.from_config(base)
+    shape_new = lz.Shape.from_config(cfg)
+    old_layer = lz.MoELayer(shape_old, DEV)
+    old_layer.load_expert_weights(w["w1"], w["w2"], old_plan)
+    layer = lz.MoELayer(shape_new, DEV)
+    n1 = w["w1"].shape[1]
+    layer.w1 = torch.zeros((shape_new.S, n1, cfg.d), dtype=torch.bfloat16, device=DEV)
+    layer.w2 = torch.zeros((shape_new.S, cfg.d, cfg.ffn), dtype=torch.bfloat16, device=DEV)
+    lz.lz_apply_transfers(got_re["transfers"], old_layer.w1, old_layer.w2, shape_old.S, layer.w1, layer.w2,
+                          shape_new.S, shape_new)
+    torch.cuda.synchronize()
+    for slot in (0, 17, shape_new.S - 1):
+        e = int(new_plan[slot])
+        assert np.array_equal(to_host(layer.w1[slot]), w["w1"][e])
+        assert np.array_equal(to_host(layer.w2[slot]), w["w2"][e])
+    del old_layer
+    torch.cuda.empty_cache()
+
+    for step in (0, 57):                            # per-step Zipf exponent drawn in [0.8, 1.5]
+        inp = step_inputs(cfg, step)
+        ids, gates = om.route(inp["logits"], cfg.k)
+        run_layer(cfg, new_plan, inp, w, layer)
+        ref = om.plan_dispatch(ids, inp["rank_tok_off"], new_plan, cfg.E, cfg.N, cfg.c)
+        check_dispatch_exact(cfg, layer, ids, ref)
+        _check_outputs(cfg, layer, inp, w, ids, gates, ref, 200, seed=step)

@@ -63,7 +63,7 @@ CONFIGS = {
     "c5_postfailure": LayerConfig(
         name="c5_postfailure", T=16384, d=2048, ffn=8192, E=32, k=2, N=6, c=8,
         dtype="bf16", act="gelu", seed=5, steps=100, bias="zipf", bias_param=1.2,
-        s_range=(0.8, 1.5), base="c3_gptmoe", base_N=8, base_c=6, drop_ranks=(2, 5)),
+        s_range=(0.8, 1.5), base="c3_gptmoe", base_N=8, base_c=6, drop_ranks=(6, 7)),
 }
 
 ORDER = ["c1_tiny", "c2_mixtral", "c3_gptmoe", "c4_finegrained", "c5_postfailure"]
