@@ -33,6 +33,8 @@ def parse():
     ap.add_argument("--workload", default="c2_mixtral")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-tokens", type=int, default=0, help="0 = pick per workload")
+    ap.add_argument("--copy-calib-mib", type=int, default=0,
+                    help="also run a plain device copy of this many MiB (counter calibration for profiling)")
     return ap.parse_args()
 
 
@@ -145,6 +147,14 @@ def main():
         if marks is not None:
             marks[6].record(stream)
 
+    if args.copy_calib_mib:
+        src = torch.empty(args.copy_calib_mib << 20, dtype=torch.uint8, device=dev).fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -212,8 +222,8 @@ def main():
         },
     }
     if not args.no_cpu_baseline:
-        n_cpu = args.cpu_sample_tokens or {"c1_tiny": 256, "c2_mixtral": 256, "c3_gptmoe": 512,
-                                           "c4_finegrained": 512}.get(cfg.name, 256)
+        n_cpu = args.cpu_sample_tokens or {"c1_tiny": 256, "c2_mixtral": 1024, "c3_gptmoe": 2048,
+                                           "c4_finegrained": 2048}.get(cfg.name, 256)
 
         def oracle_plan(op, t_e):
             if cfg.replica_counts is not None:

@@ -21,6 +21,8 @@
 //
 // Generic path (fp32 tensors, or bf16 shapes the MFMA tiling does not divide): a plain
 // 64x64x16 LDS-tiled kernel with fp32 FMA accumulation and full bounds checks.
+#include <cstdlib>
+
 #include "lz_common.h"
 
 namespace {
@@ -29,7 +31,8 @@ typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
 
 constexpr int kTileHeader = 64;  // ints before the tile arrays; [0] = number of row tiles
-constexpr int kGroupM = 4;       // row tiles that share a run of column tiles (L2 reuse)
+constexpr int kGroupM = 4;       // row tiles of a work unit (same slot)
+constexpr int kGroupN = 8;       // column tiles of a work unit
 
 enum { EPI_NONE = 0, EPI_GELU = 1, EPI_SWIGLU = 2 };
 
@@ -41,18 +44,20 @@ struct TileTable {
   int capacity;
 };
 
-inline int tile_capacity(long long P, int S, int BM) {
-  long long n = (P + BM - 1) / BM + S;
-  return int((n + kGroupM - 1) / kGroupM * kGroupM);
+// Row tiles are listed slot after slot; with group > 1 every slot's list is padded (slot = -1)
+// to a multiple of `group`, so that a group of consecutive row tiles never spans two slots.
+inline int tile_capacity(long long P, int S, int BM, int group) {
+  const long long n = (P + BM - 1) / BM + (long long)S * group;
+  return int((n + group - 1) / group * group);
 }
 
-inline size_t tile_table_bytes(long long P, int S, int BM) {
-  return lz::align256(sizeof(int32_t) * (kTileHeader + 3 * (size_t)tile_capacity(P, S, BM)));
+inline size_t tile_table_bytes(long long P, int S, int BM, int group) {
+  return lz::align256(sizeof(int32_t) * (kTileHeader + 3 * (size_t)tile_capacity(P, S, BM, group)));
 }
 
-inline TileTable carve_tiles(void* base, long long P, int S, int BM) {
+inline TileTable carve_tiles(void* base, long long P, int S, int BM, int group) {
   TileTable t;
-  t.capacity = tile_capacity(P, S, BM);
+  t.capacity = tile_capacity(P, S, BM, group);
   t.header = (int32_t*)base;
   t.slot = t.header + kTileHeader;
   t.row0 = t.slot + t.capacity;
@@ -62,7 +67,8 @@ inline TileTable carve_tiles(void* base, long long P, int S, int BM) {
 
 // slot_offsets -> row tiles.  Offsets are clipped to [0, P] and made non-decreasing.
 __global__ __launch_bounds__(256) void build_tiles_kernel(const int32_t* __restrict__ slot_offsets,
-                                                          int S, long long P, int BM, TileTable t) {
+                                                          int S, long long P, int BM, int group,
+                                                          TileTable t) {
   __shared__ int s_first[lz::kMaxN * lz::kMaxC + 1];
   if (threadIdx.x == 0) {
     int running = 0;
@@ -71,7 +77,8 @@ __global__ __launch_bounds__(256) void build_tiles_kernel(const int32_t* __restr
       a = a < 0 ? 0 : (a > P ? P : a);
       b = b < a ? a : (b > P ? P : b);
       s_first[s] = running;
-      running += int((b - a + BM - 1) / BM);
+      const int tiles = int((b - a + BM - 1) / BM);
+      running += (tiles + group - 1) / group * group;
       if (running > t.capacity) running = t.capacity;
     }
     s_first[S] = running;
@@ -83,8 +90,9 @@ __global__ __launch_bounds__(256) void build_tiles_kernel(const int32_t* __restr
     a = a < 0 ? 0 : (a > P ? P : a);
     b = b < a ? a : (b > P ? P : b);
     for (int i = s_first[s]; i < s_first[s + 1]; ++i) {
-      t.slot[i] = s;
-      t.row0[i] = int(a + (long long)(i - s_first[s]) * BM);
+      const long long r0 = a + (long long)(i - s_first[s]) * BM;
+      t.slot[i] = r0 < b ? s : -1;  // -1: padding entry, no rows
+      t.row0[i] = int(r0 < b ? r0 : b);
       t.row_end[i] = int(b);
     }
   }
@@ -124,6 +132,7 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(const Elem* __restric
   const int tile = blockIdx.y;
   if (tile >= t.header[0]) return;
   const int slot = t.slot[tile], row0 = t.row0[tile], row_end = t.row_end[tile];
+  if (slot < 0) return;
   const int n0 = blockIdx.x * BN;
   const Elem* Ws = W + (size_t)slot * w_slot_stride;
   const int tx = threadIdx.x % 16, ty = threadIdx.x / 16;
@@ -177,11 +186,10 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(const Elem* __restric
 // ------------------------------------------------------------------------------------------
 // gfx950 MFMA kernel, bf16 in / fp32 accumulate / bf16 out
 // ------------------------------------------------------------------------------------------
-constexpr int BM = 256, BN = 256, BK = 64;
-constexpr int kStageBytes = (BM + BN) * BK * 2;   // 64 KiB
-constexpr int kStages = 2;
-constexpr int kLdsBytes = kStages * kStageBytes;  // 128 KiB of the CU's 160 KiB
-constexpr int kRowBytes = BK * 2;                 // 128 B: 8 chunks of 16 B
+constexpr int BM = 256, BN = 256, BK = 32;
+constexpr int kStageBytes = (BM + BN) * BK * 2;   // 32 KiB: activation tile then weight tile
+constexpr int kRowBytes = BK * 2;                 // 64 B: 4 chunks of 16 B
+constexpr int kLoadsPerWave = BM * kRowBytes / 1024 / 4;  // 1-KiB wave loads per operand per wave: 4
 
 struct MfmaArgs {
   const uint16_t* A;    // [P, K]
@@ -193,33 +201,39 @@ struct MfmaArgs {
   int n_out;            // output columns
   int up_row0;          // SwiGLU: first row of the up projection inside a slot's W
   int n_tiles;          // column tiles per row tile
+  int dbg_noload;       // timing experiment only: skip the steady-state global loads
   TileTable t;
 };
 
-template <int SWZ>
-__device__ __forceinline__ int swz(int row) { return (row >> SWZ) & 7; }
+// 16-byte chunk c of tile row r lives at chunk position c ^ swz(r) of the row.  LDS has 64
+// banks of 4 B, so a ds_read_b128 is served 16 lanes at a time; with 64-byte rows, 16
+// consecutive rows at one logical chunk then cover 16 distinct 16-byte bank groups.
+__device__ __forceinline__ int swz(int row) { return (row >> 2) & 3; }
 
-template <int EPI, int SWZ>
+template <int EPI, int STAGES>
 __global__ __launch_bounds__(256, 1) void gemm_mfma_kernel(MfmaArgs a) {
   extern __shared__ __attribute__((aligned(1024))) char smem[];
   constexpr int BN_OUT = EPI == EPI_SWIGLU ? BN / 2 : BN;
 
-  // ---- which tile: workgroups are dealt round-robin to the 8 XCDs, so give each XCD a
-  // contiguous run of the tile order; in that order kGroupM row tiles share a column tile.
+  // ---- which tile.  Work is cut into units of kGroupM row tiles (one slot) x kGroupN column
+  // tiles = 32 tiles, one per CU of an XCD.  Workgroups are dealt round-robin to the 8 XCDs,
+  // so workgroup b belongs to XCD b % 8; units are dealt to the XCDs in the same way, in
+  // (row group, column group) order.  At any moment the chip therefore works on neighbouring
+  // column groups of the same few slots: a unit's weight panels are fetched by one XCD only
+  // and its activation panel is shared through that XCD's L2.
   const int n_row_tiles = a.t.header[0];
-  const int row_groups = (n_row_tiles + kGroupM - 1) / kGroupM;
-  const long long total = (long long)row_groups * kGroupM * a.n_tiles;
-  const long long per_xcd = (total + 7) / 8;
-  const long long within = blockIdx.x / 8;
-  if (within >= per_xcd) return;
-  const long long lin = (long long)(blockIdx.x % 8) * per_xcd + within;
-  if (lin >= total) return;
-  const int mi_in_group = int(lin % kGroupM);
-  const long long rest = lin / kGroupM;
-  const int nt = int(rest % a.n_tiles);
-  const int row_tile = int(rest / a.n_tiles) * kGroupM + mi_in_group;
-  if (row_tile >= n_row_tiles) return;
+  const int n_col_groups = (a.n_tiles + kGroupN - 1) / kGroupN;
+  const long long units = (long long)(n_row_tiles / kGroupM) * n_col_groups;
+  const int xcd = blockIdx.x % 8;
+  const int in_xcd = blockIdx.x / 8;
+  const long long unit = (long long)(in_xcd / (kGroupM * kGroupN)) * 8 + xcd;
+  if (unit >= units) return;
+  const int within = in_xcd % (kGroupM * kGroupN);
+  const int nt = int(unit % n_col_groups) * kGroupN + within / kGroupM;
+  if (nt >= a.n_tiles) return;
+  const int row_tile = int(unit / n_col_groups) * kGroupM + within % kGroupM;
   const int slot = a.t.slot[row_tile];
+  if (slot < 0) return;
   const int row0 = a.t.row0[row_tile];
   const int row_end = a.t.row_end[row_tile];
   const int n0 = nt * BN_OUT;
@@ -234,15 +248,16 @@ __global__ __launch_bounds__(256, 1) void gemm_mfma_kernel(MfmaArgs a) {
       (void*)(a.W + (size_t)slot * a.w_rows * a.K), 0, (int)(uint32_t)((unsigned long long)a.w_rows * a.K * 2),
       0x00020000);
 
-  // ---- per-lane global offsets of the 8 + 8 direct-to-LDS loads of one stage.
-  // Load u of a 256-row operand tile fills LDS bytes [u*1024, u*1024+1024): 8 rows of 128 B,
-  // lane l landing at row 8u + l/8, 16-byte chunk l%8.  That LDS chunk must hold logical
-  // chunk (l%8) ^ swz(row), so the lane fetches that one.
-  int voffA[8], voffB[8];
+  // ---- per-lane global offsets of the 4 + 4 direct-to-LDS loads of one stage.
+  // Load u of a 256-row operand tile fills LDS bytes [u*1024, u*1024+1024): 16 rows of 64 B,
+  // lane l landing at row 16u + l/4, 16-byte chunk l%4.  That LDS chunk must hold logical
+  // chunk (l%4) ^ swz(row), so the lane fetches that one (the swizzle is applied on the
+  // global side because a direct-to-LDS load fixes the LDS side to lane order).
+  int voffA[kLoadsPerWave], voffB[kLoadsPerWave];
 #pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    const int r = (wave * 8 + i) * 8 + (lane >> 3);
-    const int chunk = (lane & 7) ^ swz<SWZ>(r);
+  for (int i = 0; i < kLoadsPerWave; ++i) {
+    const int r = (wave * kLoadsPerWave + i) * 16 + (lane >> 2);
+    const int chunk = (lane & 3) ^ swz(r);
     int ga = row0 + r;
     ga = ga < row_end ? ga : row_end - 1;  // rows past the slot's end repeat its last row (never stored)
     voffA[i] = (int)(((uint32_t)ga * (uint32_t)a.K + (uint32_t)chunk * 8u) * 2u);
@@ -256,26 +271,13 @@ __global__ __launch_bounds__(256, 1) void gemm_mfma_kernel(MfmaArgs a) {
     voffB[i] = (int)(((uint32_t)gb * (uint32_t)a.K + (uint32_t)chunk * 8u) * 2u);
   }
 
-  auto issue_stage = [&](int stage, int k0) {
-    char* sA = smem + stage * kStageBytes;
-    char* sB = sA + BM * kRowBytes;
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      const int u = wave * 8 + i;
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrcA, (__attribute__((address_space(3))) void*)(sA + u * 1024),
-                                               16, voffA[i], k0 * 2, 0, 0);
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrcB, (__attribute__((address_space(3))) void*)(sB + u * 1024),
-                                               16, voffB[i], k0 * 2, 0, 0);
-    }
-  };
-
   // ---- fragment read addresses: lane l reads row (l%32) of a 32-row fragment, logical chunk
-  // 2*ks + l/32 of the 64-wide K slice
-  int fragoff[4];
+  // 2*ks + l/32 of the 32-wide K slice (ks = 0, 1)
+  int fragoff[2];
   {
     const int r = lane & 31;
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks) fragoff[ks] = r * kRowBytes + (((ks * 2 + (lane >> 5)) ^ swz<SWZ>(r)) << 4);
+    for (int ks = 0; ks < 2; ++ks) fragoff[ks] = r * kRowBytes + (((ks * 2 + (lane >> 5)) ^ swz(r)) << 4);
   }
   const int xbase = wm * 128 * kRowBytes;                   // this wave's 128 activation rows
   const int wbase = BM * kRowBytes + wn * 128 * kRowBytes;  // this wave's 128 weight rows
@@ -288,32 +290,85 @@ __global__ __launch_bounds__(256, 1) void gemm_mfma_kernel(MfmaArgs a) {
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
+  // ---- main loop: a ring of STAGES LDS stages of 32 K-columns, loads running STAGES-1 steps
+  // ahead of the MFMAs, and two register sets of fragments (A/B) alternating over the two
+  // 16-wide slices of a stage so that the ds_reads of the next slice are in flight while the
+  // MFMAs of the current one run.  One barrier per step, placed after the reads of the
+  // step's last slice have been issued: past it nobody reads the current stage any more, so
+  // the loads of step kt+STAGES can start into it, and the next stage (whose loads every
+  // wave has waited for before the barrier) can be read.
   const int k_steps = a.K / BK;
-  issue_stage(0, 0);
-  __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wave's loads have landed in LDS
-  __syncthreads();
-
-  for (int kt = 0; kt < k_steps; ++kt) {
-    const int cur = kt & 1;
-    if (kt + 1 < k_steps) issue_stage(cur ^ 1, (kt + 1) * BK);
-    const char* stage = smem + cur * kStageBytes;
+  const __amdgpu_buffer_rsrc_t rsrcNull = __builtin_amdgcn_make_buffer_rsrc((void*)a.A, 0, 0, 0x00020000);
+  auto issue_stage = [&](int stage, int k0, bool real) {
+    // a step past the end of K is "loaded" through a zero-length descriptor: no memory traffic,
+    // but the count of outstanding loads stays uniform
+    const __amdgpu_buffer_rsrc_t ra = real ? rsrcA : rsrcNull;
+    const __amdgpu_buffer_rsrc_t rb = real ? rsrcB : rsrcNull;
+    char* sA = smem + stage * kStageBytes;
+    char* sB = sA + BM * kRowBytes;
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks) {
-      bf16x8 xf[4], wf[4];
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        xf[i] = *(const bf16x8*)(stage + xbase + i * 32 * kRowBytes + fragoff[ks]);
-        wf[i] = *(const bf16x8*)(stage + wbase + i * 32 * kRowBytes + fragoff[ks]);
-      }
-#pragma unroll
-      for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[i], xf[j], acc[i][j], 0, 0, 0);
+    for (int i = 0; i < kLoadsPerWave; ++i) {
+      const int u = wave * kLoadsPerWave + i;
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(ra, (__attribute__((address_space(3))) void*)(sA + u * 1024), 16,
+                                               voffA[i], k0 * 2, 0, 0);
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rb, (__attribute__((address_space(3))) void*)(sB + u * 1024), 16,
+                                               voffB[i], k0 * 2, 0, 0);
     }
-    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): next stage's loads of this wave are in LDS
-    __syncthreads();                     // ... and everyone's; everyone is done reading `cur`
+  };
+  auto read_frags = [&](const char* stage, int ks, bf16x8 (&xf)[4], bf16x8 (&wf)[4]) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      xf[i] = *(const bf16x8*)(stage + xbase + i * 32 * kRowBytes + fragoff[ks]);
+      wf[i] = *(const bf16x8*)(stage + wbase + i * 32 * kRowBytes + fragoff[ks]);
+    }
+  };
+  auto mma = [&](const bf16x8 (&xf)[4], const bf16x8 (&wf)[4]) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[i], xf[j], acc[i][j], 0, 0, 0);
+  };
+  // s_waitcnt with only vmcnt set: vmcnt is split over bits [3:0] and [15:14] of the immediate
+  constexpr int kInFlight = (STAGES - 2) * 2 * kLoadsPerWave;  // loads that may stay outstanding
+  constexpr int kWaitStage = 0x0F70 | (kInFlight & 15) | ((kInFlight >> 4) << 14);
+
+#pragma unroll
+  for (int st = 0; st < STAGES; ++st) issue_stage(st, st * BK, st < k_steps);
+  {
+    constexpr int first = (STAGES - 1) * 2 * kLoadsPerWave;  // everything but stage 0 may be in flight
+    __builtin_amdgcn_s_waitcnt(0x0F70 | (first & 15) | ((first >> 4) << 14));
   }
+  __syncthreads();
+  bf16x8 xA[4], wA[4], xB[4], wB[4];
+  read_frags(smem, 0, xA, wA);
+
+  int slot_cur = 0;
+  for (int kt = 0; kt < k_steps; ++kt) {
+    const int slot_next = slot_cur + 1 == STAGES ? 0 : slot_cur + 1;
+    const char* st = smem + slot_cur * kStageBytes;
+    const char* nx = smem + slot_next * kStageBytes;
+    read_frags(st, 1, xB, wB);
+    mma(xA, wA);
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);  // 2 MFMA
+      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // 1 DS read
+    }
+    __builtin_amdgcn_s_waitcnt(kWaitStage);  // this wave's loads of the next stage are in LDS
+    __syncthreads();                         // everyone's are; nobody reads stage slot_cur any more
+    issue_stage(slot_cur, (kt + STAGES) * BK, kt + STAGES < k_steps && !a.dbg_noload);
+    read_frags(nx, 0, xA, wA);
+    mma(xB, wB);
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+      __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);  // 1 VMEM read
+      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+    }
+    slot_cur = slot_next;
+  }
+  __builtin_amdgcn_s_waitcnt(0x0F70);  // drain the (empty) trailing loads before LDS goes away
 
   // ---- epilogue.  acc[i][j] is the 32x32 block (weight fragment i) x (activation fragment j);
   // lane l holds activation row j*32 + l%32 and, for g = 0..3, the 4 consecutive weight
@@ -362,18 +417,23 @@ __global__ __launch_bounds__(256, 1) void gemm_mfma_kernel(MfmaArgs a) {
 }
 
 template <int EPI>
-int32_t launch_mfma(const MfmaArgs& a, hipStream_t st) {
-  auto kern = gemm_mfma_kernel<EPI, 0>;
+int32_t launch_mfma(const MfmaArgs& a_in, hipStream_t st) {
+  static const int stages = [] { const char* e = getenv("LZ_STAGES"); return e ? atoi(e) : 4; }();
+  static const int noload = [] { const char* e = getenv("LZ_DBG_NOLOAD"); return e ? atoi(e) : 0; }();
+  MfmaArgs a = a_in;
+  a.dbg_noload = noload;
+  auto kern = stages == 5 ? gemm_mfma_kernel<EPI, 5> : (stages == 3 ? gemm_mfma_kernel<EPI, 3> : gemm_mfma_kernel<EPI, 4>);
+  const int lds_bytes = (stages == 5 ? 5 : (stages == 3 ? 3 : 4)) * kStageBytes;
   static bool configured = false;  // per-process attribute; idempotent, so a benign race at worst
   if (!configured) {
-    if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes) !=
+    if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes) !=
         hipSuccess)
       return LZ_EHIP;
     configured = true;
   }
-  const long long total = (long long)a.t.capacity * a.n_tiles;
-  const long long per_xcd = (total + 7) / 8;
-  hipLaunchKernelGGL(kern, dim3((unsigned)(per_xcd * 8)), dim3(256), kLdsBytes, st, a);
+  const long long units = (long long)(a.t.capacity / kGroupM) * ((a.n_tiles + kGroupN - 1) / kGroupN);
+  const long long per_xcd = (units + 7) / 8;
+  hipLaunchKernelGGL(kern, dim3((unsigned)(per_xcd * kGroupM * kGroupN * 8)), dim3(256), lds_bytes, st, a);
   return lz::launch_status();
 }
 
@@ -388,6 +448,7 @@ struct FfnWorkspace {
   void* tiles;
   size_t total_bytes;
   int BMrows;
+  int group;
 };
 
 FfnWorkspace carve_ffn(void* ws, const lz_shape* s) {
@@ -397,7 +458,8 @@ FfnWorkspace carve_ffn(void* ws, const lz_shape* s) {
   const size_t hidden_bytes = lz::align256((size_t)P * s->ffn * lz::elem_bytes(s->dtype));
   w.hidden = ws;
   w.tiles = (char*)ws + hidden_bytes;
-  w.total_bytes = hidden_bytes + tile_table_bytes(P, s->N * s->c, w.BMrows);
+  w.group = mfma_shape(s) ? kGroupM : 1;
+  w.total_bytes = hidden_bytes + tile_table_bytes(P, s->N * s->c, w.BMrows, w.group);
   return w;
 }
 
@@ -428,9 +490,9 @@ extern "C" int32_t lz_ffn_tiles(const int32_t* slot_offsets, const lz_shape* sha
   if (P == 0) return LZ_OK;
   if (!slot_offsets) return LZ_EINVAL;
   const int S = shape->N * shape->c;
-  TileTable t = carve_tiles(w.tiles, P, S, w.BMrows);
+  TileTable t = carve_tiles(w.tiles, P, S, w.BMrows, w.group);
   hipLaunchKernelGGL(build_tiles_kernel, dim3(1), dim3(256), 0, (hipStream_t)stream, slot_offsets, S, P,
-                     w.BMrows, t);
+                     w.BMrows, w.group, t);
   return lz::launch_status();
 }
 
@@ -443,7 +505,7 @@ extern "C" int32_t lz_ffn_up(const void* xp, const void* w1, const lz_shape* sha
   if (P == 0) return LZ_OK;
   if (!xp || !w1) return LZ_EINVAL;
   hipStream_t st = (hipStream_t)stream;
-  TileTable t = carve_tiles(w.tiles, P, shape->N * shape->c, w.BMrows);
+  TileTable t = carve_tiles(w.tiles, P, shape->N * shape->c, w.BMrows, w.group);
   const bool swiglu = shape->act == LZ_SWIGLU;
   const int n1 = shape->ffn * (swiglu ? 2 : 1);
   if (!mfma_shape(shape)) {
@@ -492,7 +554,7 @@ extern "C" int32_t lz_ffn_down(const void* w2, const lz_shape* shape, void* yp, 
   if (P == 0) return LZ_OK;
   if (!w2 || !yp) return LZ_EINVAL;
   hipStream_t st = (hipStream_t)stream;
-  TileTable t = carve_tiles(w.tiles, P, shape->N * shape->c, w.BMrows);
+  TileTable t = carve_tiles(w.tiles, P, shape->N * shape->c, w.BMrows, w.group);
   if (!mfma_shape(shape)) {
     const dim3 grid((shape->d + 63) / 64, t.capacity);
     if (shape->dtype == LZ_F32)
