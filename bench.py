@@ -24,6 +24,11 @@ if ROOT not in sys.path:
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 
+# HBM bytes per launch of the dominant kernel, from the rocprofv3 FETCH_SIZE / WRITE_SIZE passes
+# summarised in profiles/<workload>_hbm_traffic.md (counters cannot be read from inside this
+# process, so the figure is carried here and re-measured whenever the kernel changes).
+MEASURED_TRAFFIC_BYTES = {"c2_mixtral": 7.78e9}
+
 
 def parse():
     ap = argparse.ArgumentParser()
@@ -186,7 +191,7 @@ def main():
     if cfg.dtype == "bf16":
         roofline = {"bound": "mfma", "kernel": "gemm_mfma_kernel (first grouped GEMM, fused activation)",
                     "achieved": tf_up, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                    "frac": tf_up / PEAK_BF16_TFLOPS, "traffic": None,
+                    "frac": tf_up / PEAK_BF16_TFLOPS, "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name),
                     "flops_per_launch": flops_up, "avg_ms": per["ffn_up"]}
     else:
         roofline = {"bound": "alu", "kernel": "gemm_generic_kernel (fp32 FMA)", "achieved": tf_up,
@@ -222,8 +227,8 @@ def main():
         },
     }
     if not args.no_cpu_baseline:
-        n_cpu = args.cpu_sample_tokens or {"c1_tiny": 256, "c2_mixtral": 1024, "c3_gptmoe": 2048,
-                                           "c4_finegrained": 2048}.get(cfg.name, 256)
+        n_cpu = args.cpu_sample_tokens or {"c1_tiny": 256, "c2_mixtral": 4096, "c3_gptmoe": 8192,
+                                           "c4_finegrained": 4096}.get(cfg.name, 256)
 
         def oracle_plan(op, t_e):
             if cfg.replica_counts is not None:

@@ -8,12 +8,13 @@
 // first turns slot_offsets into a table of row tiles (slot, first row, end row); the GEMM
 // grid is sized for the worst case and surplus workgroups exit.
 //
-// bf16 path (gfx950 MFMA): 256x256x64 workgroup tile, 4 waves in 2x2, each wave a 128x128
-// patch = 4x4 v_mfma_f32_32x32x16_bf16 accumulators (fp32).  Both operands are K-contiguous
-// and are streamed HBM -> LDS with 16-byte buffer loads that write LDS directly, double
-// buffered; the XOR swizzle that keeps the ds_read_b128 fragment reads conflict-free is
-// applied on the global-address side because a direct-to-LDS load fixes the LDS side to
-// lane order.  Buffer descriptors bound every load, so ragged tiles cannot fault.  The
+// bf16 path (gfx950 MFMA): 256x256 workgroup tile, 4 waves in 2x2, each wave a 128x128
+// patch = 4x4 v_mfma_f32_32x32x16_bf16 accumulators (fp32, 256 AGPRs).  Both operands are
+// K-contiguous and are streamed HBM -> LDS with 16-byte buffer loads that write LDS
+// directly, through a ring of LDS stages (64 K-columns x 2 stages); fragment reads are
+// software pipelined over two register sets.  The XOR swizzle that keeps the ds_read_b128
+// fragment reads conflict-free is applied on the global-address side because a
+// direct-to-LDS load fixes the LDS side to lane order.  Buffer descriptors bound every load, so ragged tiles cannot fault.  The
 // MFMA takes the weight fragment as its row operand, which leaves each lane with 4
 // consecutive output columns per accumulator group: 8-byte bf16 stores, no LDS transpose.
 // For SwiGLU the weight tile interleaves 32-row fragments of Wg and Wu, so the gate and up
@@ -186,10 +187,7 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(const Elem* __restric
 // ------------------------------------------------------------------------------------------
 // gfx950 MFMA kernel, bf16 in / fp32 accumulate / bf16 out
 // ------------------------------------------------------------------------------------------
-constexpr int BM = 256, BN = 256, BK = 32;
-constexpr int kStageBytes = (BM + BN) * BK * 2;   // 32 KiB: activation tile then weight tile
-constexpr int kRowBytes = BK * 2;                 // 64 B: 4 chunks of 16 B
-constexpr int kLoadsPerWave = BM * kRowBytes / 1024 / 4;  // 1-KiB wave loads per operand per wave: 4
+constexpr int BM = 256, BN = 256;
 
 struct MfmaArgs {
   const uint16_t* A;    // [P, K]
@@ -201,19 +199,29 @@ struct MfmaArgs {
   int n_out;            // output columns
   int up_row0;          // SwiGLU: first row of the up projection inside a slot's W
   int n_tiles;          // column tiles per row tile
-  int dbg_noload;       // timing experiment only: skip the steady-state global loads
   TileTable t;
 };
 
 // 16-byte chunk c of tile row r lives at chunk position c ^ swz(r) of the row.  LDS has 64
-// banks of 4 B, so a ds_read_b128 is served 16 lanes at a time; with 64-byte rows, 16
-// consecutive rows at one logical chunk then cover 16 distinct 16-byte bank groups.
-__device__ __forceinline__ int swz(int row) { return (row >> 2) & 3; }
+// banks of 4 B, so a ds_read_b128 is served 16 lanes at a time: 16 consecutive rows at one
+// logical chunk must cover 16 distinct 16-byte bank groups (256 B).  With 64-byte rows
+// (BK = 32) four rows fill 256 B, so the swizzle key is row/4; with 128-byte rows, row/2.
+template <int BK>
+__device__ __forceinline__ int swz(int row) {
+  return BK == 32 ? ((row >> 2) & 3) : ((row >> 1) & 7);
+}
 
-template <int EPI, int STAGES>
+template <int EPI, int BK, int STAGES>
 __global__ __launch_bounds__(256, 1) void gemm_mfma_kernel(MfmaArgs a) {
+#if defined(__HIP_DEVICE_COMPILE__)  // the host pass only needs the launch stub, not the gfx950 builtins
   extern __shared__ __attribute__((aligned(1024))) char smem[];
   constexpr int BN_OUT = EPI == EPI_SWIGLU ? BN / 2 : BN;
+  constexpr int kRowBytes = BK * 2;                     // bytes of one tile row in LDS
+  constexpr int kChunks = kRowBytes / 16;               // 16-byte chunks per row
+  constexpr int kStageBytes = (BM + BN) * kRowBytes;    // activation tile, then weight tile
+  constexpr int kLoadsPerWave = BM * kRowBytes / 1024 / 4;  // 1-KiB wave loads per operand per wave
+  constexpr int kRowsPerLoad = 1024 / kRowBytes;
+  constexpr int KS = BK / 16;                           // 16-wide MFMA slices per stage
 
   // ---- which tile.  Work is cut into units of kGroupM row tiles (one slot) x kGroupN column
   // tiles = 32 tiles, one per CU of an XCD.  Workgroups are dealt round-robin to the 8 XCDs,
@@ -248,16 +256,16 @@ __global__ __launch_bounds__(256, 1) void gemm_mfma_kernel(MfmaArgs a) {
       (void*)(a.W + (size_t)slot * a.w_rows * a.K), 0, (int)(uint32_t)((unsigned long long)a.w_rows * a.K * 2),
       0x00020000);
 
-  // ---- per-lane global offsets of the 4 + 4 direct-to-LDS loads of one stage.
-  // Load u of a 256-row operand tile fills LDS bytes [u*1024, u*1024+1024): 16 rows of 64 B,
-  // lane l landing at row 16u + l/4, 16-byte chunk l%4.  That LDS chunk must hold logical
-  // chunk (l%4) ^ swz(row), so the lane fetches that one (the swizzle is applied on the
-  // global side because a direct-to-LDS load fixes the LDS side to lane order).
+  // ---- per-lane global offsets of the direct-to-LDS loads of one stage.
+  // Load u of a 256-row operand tile fills LDS bytes [u*1024, u*1024+1024): whole rows, lane l
+  // landing at row u*kRowsPerLoad + l/kChunks, 16-byte chunk l%kChunks.  That LDS chunk must
+  // hold logical chunk (l%kChunks) ^ swz(row), so the lane fetches that one (the swizzle is
+  // applied on the global side because a direct-to-LDS load fixes the LDS side to lane order).
   int voffA[kLoadsPerWave], voffB[kLoadsPerWave];
 #pragma unroll
   for (int i = 0; i < kLoadsPerWave; ++i) {
-    const int r = (wave * kLoadsPerWave + i) * 16 + (lane >> 2);
-    const int chunk = (lane & 3) ^ swz(r);
+    const int r = (wave * kLoadsPerWave + i) * kRowsPerLoad + lane / kChunks;
+    const int chunk = (lane % kChunks) ^ swz<BK>(r);
     int ga = row0 + r;
     ga = ga < row_end ? ga : row_end - 1;  // rows past the slot's end repeat its last row (never stored)
     voffA[i] = (int)(((uint32_t)ga * (uint32_t)a.K + (uint32_t)chunk * 8u) * 2u);
@@ -272,12 +280,12 @@ __global__ __launch_bounds__(256, 1) void gemm_mfma_kernel(MfmaArgs a) {
   }
 
   // ---- fragment read addresses: lane l reads row (l%32) of a 32-row fragment, logical chunk
-  // 2*ks + l/32 of the 32-wide K slice (ks = 0, 1)
-  int fragoff[2];
+  // 2*ks + l/32 of the stage's K slice
+  int fragoff[KS];
   {
     const int r = lane & 31;
 #pragma unroll
-    for (int ks = 0; ks < 2; ++ks) fragoff[ks] = r * kRowBytes + (((ks * 2 + (lane >> 5)) ^ swz(r)) << 4);
+    for (int ks = 0; ks < KS; ++ks) fragoff[ks] = r * kRowBytes + (((ks * 2 + (lane >> 5)) ^ swz<BK>(r)) << 4);
   }
   const int xbase = wm * 128 * kRowBytes;                   // this wave's 128 activation rows
   const int wbase = BM * kRowBytes + wn * 128 * kRowBytes;  // this wave's 128 weight rows
@@ -290,80 +298,94 @@ __global__ __launch_bounds__(256, 1) void gemm_mfma_kernel(MfmaArgs a) {
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-  // ---- main loop: a ring of STAGES LDS stages of 32 K-columns, loads running STAGES-1 steps
-  // ahead of the MFMAs, and two register sets of fragments (A/B) alternating over the two
-  // 16-wide slices of a stage so that the ds_reads of the next slice are in flight while the
-  // MFMAs of the current one run.  One barrier per step, placed after the reads of the
-  // step's last slice have been issued: past it nobody reads the current stage any more, so
-  // the loads of step kt+STAGES can start into it, and the next stage (whose loads every
-  // wave has waited for before the barrier) can be read.
+  // ---- main loop: a ring of STAGES LDS stages of BK K-columns, loads running STAGES-1 steps
+  // ahead of the MFMAs, and two register sets of fragments alternating over the 16-wide
+  // slices so that the ds_reads of the next slice are in flight while the MFMAs of the
+  // current one run.  One barrier per step, placed after the reads of the step's last slice
+  // have been issued: past it nobody reads the current stage any more, so the loads of step
+  // kt+STAGES can start into it, and the next stage (whose loads every wave has waited for
+  // before the barrier) can be read.
   const int k_steps = a.K / BK;
   const __amdgpu_buffer_rsrc_t rsrcNull = __builtin_amdgcn_make_buffer_rsrc((void*)a.A, 0, 0, 0x00020000);
-  auto issue_stage = [&](int stage, int k0, bool real) {
-    // a step past the end of K is "loaded" through a zero-length descriptor: no memory traffic,
-    // but the count of outstanding loads stays uniform
+  // a step past the end of K is "loaded" through a zero-length descriptor: no memory traffic,
+  // but the count of outstanding loads stays uniform
+  auto issue_x = [&](int stage, int k0, bool real) {
     const __amdgpu_buffer_rsrc_t ra = real ? rsrcA : rsrcNull;
-    const __amdgpu_buffer_rsrc_t rb = real ? rsrcB : rsrcNull;
     char* sA = smem + stage * kStageBytes;
-    char* sB = sA + BM * kRowBytes;
 #pragma unroll
     for (int i = 0; i < kLoadsPerWave; ++i) {
       const int u = wave * kLoadsPerWave + i;
       __builtin_amdgcn_raw_ptr_buffer_load_lds(ra, (__attribute__((address_space(3))) void*)(sA + u * 1024), 16,
                                                voffA[i], k0 * 2, 0, 0);
+    }
+  };
+  auto issue_w = [&](int stage, int k0, bool real) {
+    const __amdgpu_buffer_rsrc_t rb = real ? rsrcB : rsrcNull;
+    char* sB = smem + stage * kStageBytes + BM * kRowBytes;
+#pragma unroll
+    for (int i = 0; i < kLoadsPerWave; ++i) {
+      const int u = wave * kLoadsPerWave + i;
       __builtin_amdgcn_raw_ptr_buffer_load_lds(rb, (__attribute__((address_space(3))) void*)(sB + u * 1024), 16,
                                                voffB[i], k0 * 2, 0, 0);
     }
   };
-  auto read_frags = [&](const char* stage, int ks, bf16x8 (&xf)[4], bf16x8 (&wf)[4]) {
+  bf16x8 xf[2][4], wf[2][4];
+  auto read_frags = [&](const char* stage, int ks, int set) {
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      xf[i] = *(const bf16x8*)(stage + xbase + i * 32 * kRowBytes + fragoff[ks]);
-      wf[i] = *(const bf16x8*)(stage + wbase + i * 32 * kRowBytes + fragoff[ks]);
+      xf[set][i] = *(const bf16x8*)(stage + xbase + i * 32 * kRowBytes + fragoff[ks]);
+      wf[set][i] = *(const bf16x8*)(stage + wbase + i * 32 * kRowBytes + fragoff[ks]);
     }
   };
-  auto mma = [&](const bf16x8 (&xf)[4], const bf16x8 (&wf)[4]) {
+  auto mma = [&](int set) {
 #pragma unroll
     for (int i = 0; i < 4; ++i)
 #pragma unroll
       for (int j = 0; j < 4; ++j)
-        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[i], xf[j], acc[i][j], 0, 0, 0);
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[set][i], xf[set][j], acc[i][j], 0, 0, 0);
   };
   // s_waitcnt with only vmcnt set: vmcnt is split over bits [3:0] and [15:14] of the immediate
   constexpr int kInFlight = (STAGES - 2) * 2 * kLoadsPerWave;  // loads that may stay outstanding
   constexpr int kWaitStage = 0x0F70 | (kInFlight & 15) | ((kInFlight >> 4) << 14);
 
 #pragma unroll
-  for (int st = 0; st < STAGES; ++st) issue_stage(st, st * BK, st < k_steps);
+  for (int st = 0; st < STAGES; ++st) {
+    issue_x(st, st * BK, st < k_steps);
+    issue_w(st, st * BK, st < k_steps);
+  }
   {
     constexpr int first = (STAGES - 1) * 2 * kLoadsPerWave;  // everything but stage 0 may be in flight
     __builtin_amdgcn_s_waitcnt(0x0F70 | (first & 15) | ((first >> 4) << 14));
   }
   __syncthreads();
-  bf16x8 xA[4], wA[4], xB[4], wB[4];
-  read_frags(smem, 0, xA, wA);
+  read_frags(smem, 0, 0);
 
   int slot_cur = 0;
   for (int kt = 0; kt < k_steps; ++kt) {
     const int slot_next = slot_cur + 1 == STAGES ? 0 : slot_cur + 1;
     const char* st = smem + slot_cur * kStageBytes;
     const char* nx = smem + slot_next * kStageBytes;
-    read_frags(st, 1, xB, wB);
-    mma(xA, wA);
 #pragma unroll
-    for (int q = 0; q < 8; ++q) {
-      __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);  // 2 MFMA
-      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // 1 DS read
+    for (int ks = 0; ks < KS - 1; ++ks) {
+      read_frags(st, ks + 1, (ks + 1) & 1);
+      mma(ks & 1);
+#pragma unroll
+      for (int q = 0; q < 8; ++q) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);  // 2 MFMA
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // 1 DS read
+      }
     }
     __builtin_amdgcn_s_waitcnt(kWaitStage);  // this wave's loads of the next stage are in LDS
     __syncthreads();                         // everyone's are; nobody reads stage slot_cur any more
-    issue_stage(slot_cur, (kt + STAGES) * BK, kt + STAGES < k_steps && !a.dbg_noload);
-    read_frags(nx, 0, xA, wA);
-    mma(xB, wB);
+    const bool more = kt + STAGES < k_steps;
+    issue_x(slot_cur, (kt + STAGES) * BK, more);
+    issue_w(slot_cur, (kt + STAGES) * BK, more);
+    read_frags(nx, 0, 0);
+    mma((KS - 1) & 1);
 #pragma unroll
     for (int q = 0; q < 8; ++q) {
       __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
-      __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);  // 1 VMEM read
+      __builtin_amdgcn_sched_group_barrier(0x020, kLoadsPerWave / 4, 0);  // VMEM reads
       __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
     }
     slot_cur = slot_next;
@@ -414,16 +436,15 @@ __global__ __launch_bounds__(256, 1) void gemm_mfma_kernel(MfmaArgs a) {
         }
     }
   }
+#endif
 }
 
 template <int EPI>
-int32_t launch_mfma(const MfmaArgs& a_in, hipStream_t st) {
-  static const int stages = [] { const char* e = getenv("LZ_STAGES"); return e ? atoi(e) : 4; }();
-  static const int noload = [] { const char* e = getenv("LZ_DBG_NOLOAD"); return e ? atoi(e) : 0; }();
-  MfmaArgs a = a_in;
-  a.dbg_noload = noload;
-  auto kern = stages == 5 ? gemm_mfma_kernel<EPI, 5> : (stages == 3 ? gemm_mfma_kernel<EPI, 3> : gemm_mfma_kernel<EPI, 4>);
-  const int lds_bytes = (stages == 5 ? 5 : (stages == 3 ? 3 : 4)) * kStageBytes;
+int32_t launch_mfma(const MfmaArgs& a, hipStream_t st) {
+  // LZ_GEMM_VARIANT: 0 (default) = 64-wide stages in a 2-deep ring; 1 = 32-wide stages, 4-deep
+  static const int variant = [] { const char* e = getenv("LZ_GEMM_VARIANT"); return e ? atoi(e) : 0; }();
+  void (*kern)(MfmaArgs) = variant == 1 ? gemm_mfma_kernel<EPI, 32, 4> : gemm_mfma_kernel<EPI, 64, 2>;
+  const int lds_bytes = 128 * 1024;
   static bool configured = false;  // per-process attribute; idempotent, so a benign race at worst
   if (!configured) {
     if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes) !=
@@ -439,7 +460,7 @@ int32_t launch_mfma(const MfmaArgs& a_in, hipStream_t st) {
 
 inline bool mfma_shape(const lz_shape* s) {
   if (s->dtype != LZ_BF16) return false;
-  if (s->d % BN != 0 || s->d % BK != 0 || s->ffn % BK != 0) return false;
+  if (s->d % BN != 0 || s->ffn % 64 != 0) return false;
   return s->ffn % (s->act == LZ_SWIGLU ? BN / 2 : BN) == 0;
 }
 
