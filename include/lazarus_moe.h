@@ -127,7 +127,8 @@ int32_t lz_permute(const void* x, const int32_t* row_to_pair, const lz_shape* sh
 /* Expert FFN over the permuted buffer (Sec. 2.1: experts are parallel FFNs; each replica
  * processes the tokens dispatched to it).  Rows [slot_offsets[s], slot_offsets[s+1]) use
  * the weights of slot s:
- *   LZ_GELU    yp = gelu(xp W1^T) W2^T          gelu exact: 0.5 v (1 + erf(v/sqrt 2))
+ *   LZ_GELU    yp = gelu(xp W1^T) W2^T          gelu = 0.5 v (1 + erf(v/sqrt 2)), the erf form (not tanh);
+ *                                                fp32 path: erff; bf16 MFMA path: erf to < 1e-6 absolute
  *   LZ_SWIGLU  yp = (silu(xp Wg^T) * (xp Wu^T)) W2^T
  *   w1  dev [S, n1, d]   n1 = ffn (GELU) or 2*ffn (SwiGLU: rows [0,ffn) = Wg, [ffn,2ffn) = Wu)
  *   w2  dev [S, d, ffn]

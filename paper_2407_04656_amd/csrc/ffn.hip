@@ -22,8 +22,6 @@
 //
 // Generic path (fp32 tensors, or bf16 shapes the MFMA tiling does not divide): a plain
 // 64x64x16 LDS-tiled kernel with fp32 FMA accumulation and full bounds checks.
-#include <cstdlib>
-
 #include "lz_common.h"
 
 namespace {
@@ -187,7 +185,10 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(const Elem* __restric
 // ------------------------------------------------------------------------------------------
 // gfx950 MFMA kernel, bf16 in / fp32 accumulate / bf16 out
 // ------------------------------------------------------------------------------------------
-constexpr int BM = 256, BN = 256;
+constexpr int BM = 256, BN = 256, BK = 64;
+constexpr int kRowBytes = BK * 2;                  // one tile row of a stage in LDS: 128 B = 8 chunks of 16 B
+constexpr int kStageBytes = (BM + BN) * kRowBytes; // activation tile (up to 256 rows), then weight tile; 2 stages
+constexpr int kLdsBytes = 2 * kStageBytes;          // 128 KiB of the CU's 160 KiB
 
 struct MfmaArgs {
   const uint16_t* A;    // [P, K]
@@ -202,26 +203,232 @@ struct MfmaArgs {
   TileTable t;
 };
 
-// 16-byte chunk c of tile row r lives at chunk position c ^ swz(r) of the row.  LDS has 64
-// banks of 4 B, so a ds_read_b128 is served 16 lanes at a time: 16 consecutive rows at one
-// logical chunk must cover 16 distinct 16-byte bank groups (256 B).  With 64-byte rows
-// (BK = 32) four rows fill 256 B, so the swizzle key is row/4; with 128-byte rows, row/2.
-template <int BK>
-__device__ __forceinline__ int swz(int row) {
-  return BK == 32 ? ((row >> 2) & 3) : ((row >> 1) & 7);
+// Activations on the fp32 accumulators of the bf16 path.  The result is rounded to bf16
+// (relative step 2^-9), so hardware exp2 / rcp (1 ulp) are used; erf is the
+// Abramowitz-Stegun 7.1.26 rational form, absolute error below 2e-7 before those.
+__device__ __forceinline__ float silu_fast(float v) {
+  return v * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.44269504088896341f * v));
+}
+__device__ __forceinline__ float gelu_fast(float v) {
+  const float x = fabsf(v) * 0.70710678118654752440f;
+  const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f, x, 1.0f));
+  float p = fmaf(1.061405429f, t, -1.453152027f);
+  p = fmaf(p, t, 1.421413741f);
+  p = fmaf(p, t, -0.284496736f);
+  p = fmaf(p, t, 0.254829592f);
+  const float e = __builtin_amdgcn_exp2f(-1.44269504088896341f * x * x);
+  const float erf_abs = 1.0f - p * t * e;         // erf(|v| / sqrt 2)
+  return 0.5f * v + 0.5f * fabsf(v) * erf_abs;    // 0.5 v (1 + sign(v) erf_abs)
 }
 
-template <int EPI, int BK, int STAGES>
+// 16-byte chunk c of tile row r lives at chunk position c ^ swz(r) of its 128-byte LDS row.
+// LDS has 64 banks of 4 B, so a ds_read_b128 is served 16 lanes at a time: 16 consecutive
+// rows at one logical chunk must cover 16 distinct 16-byte bank groups (256 B = 2 rows), hence
+// the key row/2.
+__device__ __forceinline__ int swz(int row) { return (row >> 1) & 7; }
+
+// Scheduling hint for one 16-wide K slice: ND ds_reads spread evenly through NM MFMAs.
+template <int Q, int ND, int NM>
+__device__ __forceinline__ void sched_mfma_ds() {
+  if constexpr (Q < ND) {
+    constexpr int m = (NM * (Q + 1)) / ND - (NM * Q) / ND;
+    if constexpr (m > 0) __builtin_amdgcn_sched_group_barrier(0x008, m, 0);  // MFMA
+    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                        // DS read
+    sched_mfma_ds<Q + 1, ND, NM>();
+  }
+}
+
+// One output tile of 64*XF rows x 256 weight rows.  XF = 32-row activation fragments per
+// wave: the 2x2 waves each own (32*XF) x 128 of the tile, so a slot's ragged last tile costs
+// MFMAs and activation loads only for its rows rounded up to 64.
+template <int EPI, int XF>
+__device__ __forceinline__ void gemm_tile(const MfmaArgs& a, char* smem, int slot, int row0, int row_end, int n0) {
+  constexpr int KS = BK / 16;             // 16-wide MFMA slices per stage
+  constexpr int kLoadsX = 2 * XF;         // 1-KiB wave loads per wave for the activation tile (8 rows each)
+  constexpr int kLoadsW = 8;              // ... for the 256-row weight tile
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+
+  // ---- buffer descriptors: out-of-range loads return zero instead of faulting
+  const __amdgpu_buffer_rsrc_t rsrcA = __builtin_amdgcn_make_buffer_rsrc(
+      (void*)a.A, 0, (int)(uint32_t)((unsigned long long)a.P * a.K * 2), 0x00020000);
+  const __amdgpu_buffer_rsrc_t rsrcB = __builtin_amdgcn_make_buffer_rsrc(
+      (void*)(a.W + (size_t)slot * a.w_rows * a.K), 0, (int)(uint32_t)((unsigned long long)a.w_rows * a.K * 2),
+      0x00020000);
+  const __amdgpu_buffer_rsrc_t rsrcNull = __builtin_amdgcn_make_buffer_rsrc((void*)a.A, 0, 0, 0x00020000);
+
+  // ---- per-lane global offsets of the direct-to-LDS loads of one stage.
+  // Load u of an operand tile fills LDS bytes [u*1024, u*1024+1024): 8 whole rows, lane l
+  // landing at row 8u + l/8, 16-byte chunk l%8.  That LDS chunk must hold logical chunk
+  // (l%8) ^ swz(row), so the lane fetches that one (the swizzle is applied on the global side
+  // because a direct-to-LDS load fixes the LDS side to lane order).
+  int voffX[kLoadsX], voffW[kLoadsW];
+#pragma unroll
+  for (int i = 0; i < kLoadsX; ++i) {
+    const int r = (wave * kLoadsX + i) * 8 + (lane >> 3);
+    const int chunk = (lane & 7) ^ swz(r);
+    int ga = row0 + r;
+    ga = ga < row_end ? ga : row_end - 1;  // rows past the slot's end repeat its last row (never stored)
+    voffX[i] = (int)(((uint32_t)ga * (uint32_t)a.K + (uint32_t)chunk * 8u) * 2u);
+  }
+#pragma unroll
+  for (int i = 0; i < kLoadsW; ++i) {
+    const int r = (wave * kLoadsW + i) * 8 + (lane >> 3);
+    const int chunk = (lane & 7) ^ swz(r);
+    int gb;
+    if (EPI == EPI_SWIGLU) {
+      const int f = r >> 5;  // fragment index: even = gate rows, odd = up rows
+      gb = n0 + (f >> 1) * 32 + (r & 31) + ((f & 1) ? a.up_row0 : 0);
+    } else {
+      gb = n0 + r;
+    }
+    voffW[i] = (int)(((uint32_t)gb * (uint32_t)a.K + (uint32_t)chunk * 8u) * 2u);
+  }
+
+  // ---- fragment read addresses: lane l reads row (l%32) of a 32-row fragment, logical chunk
+  // 2*ks + l/32 of the stage's K slice
+  int fragoff[KS];
+  {
+    const int r = lane & 31;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) fragoff[ks] = r * kRowBytes + (((ks * 2 + (lane >> 5)) ^ swz(r)) << 4);
+  }
+  const int xbase = wm * 32 * XF * kRowBytes;               // this wave's activation rows
+  const int wbase = BM * kRowBytes + wn * 128 * kRowBytes;  // this wave's 128 weight rows
+
+  f32x16 acc[4][XF];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < XF; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+  // ---- main loop: two LDS stages of 64 K-columns, the loads of step kt+2 issued as soon as
+  // stage kt is free, and two register sets of fragments alternating over the four 16-wide
+  // slices so that the ds_reads of the next slice are in flight while the MFMAs of the
+  // current one run.  One barrier per step, placed after the reads of the step's last slice
+  // have been issued: past it nobody reads the current stage any more, so the loads of step
+  // kt+2 can start into it, and the next stage (whose loads every wave has waited for before
+  // the barrier) can be read.
+  const int k_steps = a.K / BK;
+  auto issue_stage = [&](int stage, int step) {
+    // a step past the end of K is "loaded" through a zero-length descriptor: no memory traffic
+    const bool real = step < k_steps;
+    const __amdgpu_buffer_rsrc_t ra = real ? rsrcA : rsrcNull;
+    const __amdgpu_buffer_rsrc_t rb = real ? rsrcB : rsrcNull;
+    char* sX = smem + stage * kStageBytes;
+    char* sW = sX + BM * kRowBytes;
+#pragma unroll
+    for (int i = 0; i < kLoadsW; ++i) {
+      const int u = wave * kLoadsW + i;
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rb, (__attribute__((address_space(3))) void*)(sW + u * 1024), 16,
+                                               voffW[i], step * BK * 2, 0, 0);
+    }
+#pragma unroll
+    for (int i = 0; i < kLoadsX; ++i) {
+      const int u = wave * kLoadsX + i;
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(ra, (__attribute__((address_space(3))) void*)(sX + u * 1024), 16,
+                                               voffX[i], step * BK * 2, 0, 0);
+    }
+  };
+  bf16x8 xf[2][XF], wf[2][4];
+  auto read_frags = [&](const char* stage, int ks, int set) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) wf[set][i] = *(const bf16x8*)(stage + wbase + i * 32 * kRowBytes + fragoff[ks]);
+#pragma unroll
+    for (int j = 0; j < XF; ++j) xf[set][j] = *(const bf16x8*)(stage + xbase + j * 32 * kRowBytes + fragoff[ks]);
+  };
+  auto mma = [&](int set) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int j = 0; j < XF; ++j)
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[set][i], xf[set][j], acc[i][j], 0, 0, 0);
+  };
+
+  issue_stage(0, 0);
+  issue_stage(1, 1);
+  {
+    // s_waitcnt with only vmcnt set (bits [3:0] and [15:14]): stage 1 may still be in flight
+    constexpr int n = kLoadsX + kLoadsW;
+    __builtin_amdgcn_s_waitcnt(0x0F70 | (n & 15) | ((n >> 4) << 14));
+  }
+  __syncthreads();
+  read_frags(smem, 0, 0);
+
+  for (int kt = 0; kt < k_steps; ++kt) {
+    const int cur = kt & 1;
+    const char* st = smem + cur * kStageBytes;
+    const char* nx = smem + (cur ^ 1) * kStageBytes;
+#pragma unroll
+    for (int ks = 0; ks < KS - 1; ++ks) {
+      read_frags(st, ks + 1, (ks + 1) & 1);
+      mma(ks & 1);
+      sched_mfma_ds<0, 4 + XF, 4 * XF>();
+    }
+    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wave's loads of the next stage are in LDS
+    __syncthreads();                     // everyone's are; nobody reads stage `cur` any more
+    issue_stage(cur, kt + 2);
+    read_frags(nx, 0, 0);
+    mma((KS - 1) & 1);
+    // all loads of the freed stage go out first: the last one to land gates the next barrier
+    __builtin_amdgcn_sched_group_barrier(0x020, kLoadsX + kLoadsW, 0);
+    sched_mfma_ds<0, 4 + XF, 4 * XF>();
+  }
+  __builtin_amdgcn_s_waitcnt(0x0F70);  // drain the (empty) trailing loads before LDS goes away
+
+  // ---- epilogue.  acc[i][j] is the 32x32 block (weight fragment i) x (activation fragment j);
+  // lane l holds activation row j*32 + l%32 and, for g = 0..3, the 4 consecutive weight rows
+  // i*32 + 8g + 4*(l/32) + 0..3  -> 4 consecutive output columns, one 8-byte bf16 store.
+  const int half = lane >> 5;
+#pragma unroll
+  for (int j = 0; j < XF; ++j) {
+    const int row = row0 + wm * 32 * XF + j * 32 + (lane & 31);
+    if (row >= row_end) continue;
+    uint16_t* crow = a.C + (size_t)row * a.n_out;
+    if (EPI == EPI_SWIGLU) {
+#pragma unroll
+      for (int q = 0; q < 2; ++q)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const int col = n0 + wn * 64 + q * 32 + 8 * g + 4 * half;
+          uint16_t o[4];
+#pragma unroll
+          for (int r = 0; r < 4; ++r)
+            o[r] = lz::f32_to_bf16(silu_fast(acc[2 * q][j][4 * g + r]) * acc[2 * q + 1][j][4 * g + r]);
+          uint2 pk;
+          pk.x = uint32_t(o[0]) | (uint32_t(o[1]) << 16);
+          pk.y = uint32_t(o[2]) | (uint32_t(o[3]) << 16);
+          *(uint2*)(crow + col) = pk;
+        }
+    } else {
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const int col = n0 + wn * 128 + i * 32 + 8 * g + 4 * half;
+          uint16_t o[4];
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            float v = acc[i][j][4 * g + r];
+            if (EPI == EPI_GELU) v = gelu_fast(v);
+            o[r] = lz::f32_to_bf16(v);
+          }
+          uint2 pk;
+          pk.x = uint32_t(o[0]) | (uint32_t(o[1]) << 16);
+          pk.y = uint32_t(o[2]) | (uint32_t(o[3]) << 16);
+          *(uint2*)(crow + col) = pk;
+        }
+    }
+  }
+}
+
+template <int EPI>
 __global__ __launch_bounds__(256, 1) void gemm_mfma_kernel(MfmaArgs a) {
 #if defined(__HIP_DEVICE_COMPILE__)  // the host pass only needs the launch stub, not the gfx950 builtins
   extern __shared__ __attribute__((aligned(1024))) char smem[];
   constexpr int BN_OUT = EPI == EPI_SWIGLU ? BN / 2 : BN;
-  constexpr int kRowBytes = BK * 2;                     // bytes of one tile row in LDS
-  constexpr int kChunks = kRowBytes / 16;               // 16-byte chunks per row
-  constexpr int kStageBytes = (BM + BN) * kRowBytes;    // activation tile, then weight tile
-  constexpr int kLoadsPerWave = BM * kRowBytes / 1024 / 4;  // 1-KiB wave loads per operand per wave
-  constexpr int kRowsPerLoad = 1024 / kRowBytes;
-  constexpr int KS = BK / 16;                           // 16-wide MFMA slices per stage
 
   // ---- which tile.  Work is cut into units of kGroupM row tiles (one slot) x kGroupN column
   // tiles = 32 tiles, one per CU of an XCD.  Workgroups are dealt round-robin to the 8 XCDs,
@@ -245,216 +452,27 @@ __global__ __launch_bounds__(256, 1) void gemm_mfma_kernel(MfmaArgs a) {
   const int row0 = a.t.row0[row_tile];
   const int row_end = a.t.row_end[row_tile];
   const int n0 = nt * BN_OUT;
-
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wm = wave >> 1, wn = wave & 1;
-
-  // ---- buffer descriptors: out-of-range loads return zero instead of faulting
-  const __amdgpu_buffer_rsrc_t rsrcA = __builtin_amdgcn_make_buffer_rsrc(
-      (void*)a.A, 0, (int)(uint32_t)((unsigned long long)a.P * a.K * 2), 0x00020000);
-  const __amdgpu_buffer_rsrc_t rsrcB = __builtin_amdgcn_make_buffer_rsrc(
-      (void*)(a.W + (size_t)slot * a.w_rows * a.K), 0, (int)(uint32_t)((unsigned long long)a.w_rows * a.K * 2),
-      0x00020000);
-
-  // ---- per-lane global offsets of the direct-to-LDS loads of one stage.
-  // Load u of a 256-row operand tile fills LDS bytes [u*1024, u*1024+1024): whole rows, lane l
-  // landing at row u*kRowsPerLoad + l/kChunks, 16-byte chunk l%kChunks.  That LDS chunk must
-  // hold logical chunk (l%kChunks) ^ swz(row), so the lane fetches that one (the swizzle is
-  // applied on the global side because a direct-to-LDS load fixes the LDS side to lane order).
-  int voffA[kLoadsPerWave], voffB[kLoadsPerWave];
-#pragma unroll
-  for (int i = 0; i < kLoadsPerWave; ++i) {
-    const int r = (wave * kLoadsPerWave + i) * kRowsPerLoad + lane / kChunks;
-    const int chunk = (lane % kChunks) ^ swz<BK>(r);
-    int ga = row0 + r;
-    ga = ga < row_end ? ga : row_end - 1;  // rows past the slot's end repeat its last row (never stored)
-    voffA[i] = (int)(((uint32_t)ga * (uint32_t)a.K + (uint32_t)chunk * 8u) * 2u);
-    int gb;
-    if (EPI == EPI_SWIGLU) {
-      const int f = r >> 5;  // fragment index: even = gate rows, odd = up rows
-      gb = n0 + (f >> 1) * 32 + (r & 31) + ((f & 1) ? a.up_row0 : 0);
-    } else {
-      gb = n0 + r;
-    }
-    voffB[i] = (int)(((uint32_t)gb * (uint32_t)a.K + (uint32_t)chunk * 8u) * 2u);
-  }
-
-  // ---- fragment read addresses: lane l reads row (l%32) of a 32-row fragment, logical chunk
-  // 2*ks + l/32 of the stage's K slice
-  int fragoff[KS];
-  {
-    const int r = lane & 31;
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks) fragoff[ks] = r * kRowBytes + (((ks * 2 + (lane >> 5)) ^ swz<BK>(r)) << 4);
-  }
-  const int xbase = wm * 128 * kRowBytes;                   // this wave's 128 activation rows
-  const int wbase = BM * kRowBytes + wn * 128 * kRowBytes;  // this wave's 128 weight rows
-
-  f32x16 acc[4][4];
-#pragma unroll
-  for (int i = 0; i < 4; ++i)
-#pragma unroll
-    for (int j = 0; j < 4; ++j)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
-
-  // ---- main loop: a ring of STAGES LDS stages of BK K-columns, loads running STAGES-1 steps
-  // ahead of the MFMAs, and two register sets of fragments alternating over the 16-wide
-  // slices so that the ds_reads of the next slice are in flight while the MFMAs of the
-  // current one run.  One barrier per step, placed after the reads of the step's last slice
-  // have been issued: past it nobody reads the current stage any more, so the loads of step
-  // kt+STAGES can start into it, and the next stage (whose loads every wave has waited for
-  // before the barrier) can be read.
-  const int k_steps = a.K / BK;
-  const __amdgpu_buffer_rsrc_t rsrcNull = __builtin_amdgcn_make_buffer_rsrc((void*)a.A, 0, 0, 0x00020000);
-  // a step past the end of K is "loaded" through a zero-length descriptor: no memory traffic,
-  // but the count of outstanding loads stays uniform
-  auto issue_x = [&](int stage, int k0, bool real) {
-    const __amdgpu_buffer_rsrc_t ra = real ? rsrcA : rsrcNull;
-    char* sA = smem + stage * kStageBytes;
-#pragma unroll
-    for (int i = 0; i < kLoadsPerWave; ++i) {
-      const int u = wave * kLoadsPerWave + i;
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(ra, (__attribute__((address_space(3))) void*)(sA + u * 1024), 16,
-                                               voffA[i], k0 * 2, 0, 0);
-    }
-  };
-  auto issue_w = [&](int stage, int k0, bool real) {
-    const __amdgpu_buffer_rsrc_t rb = real ? rsrcB : rsrcNull;
-    char* sB = smem + stage * kStageBytes + BM * kRowBytes;
-#pragma unroll
-    for (int i = 0; i < kLoadsPerWave; ++i) {
-      const int u = wave * kLoadsPerWave + i;
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(rb, (__attribute__((address_space(3))) void*)(sB + u * 1024), 16,
-                                               voffB[i], k0 * 2, 0, 0);
-    }
-  };
-  bf16x8 xf[2][4], wf[2][4];
-  auto read_frags = [&](const char* stage, int ks, int set) {
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      xf[set][i] = *(const bf16x8*)(stage + xbase + i * 32 * kRowBytes + fragoff[ks]);
-      wf[set][i] = *(const bf16x8*)(stage + wbase + i * 32 * kRowBytes + fragoff[ks]);
-    }
-  };
-  auto mma = [&](int set) {
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-      for (int j = 0; j < 4; ++j)
-        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[set][i], xf[set][j], acc[i][j], 0, 0, 0);
-  };
-  // s_waitcnt with only vmcnt set: vmcnt is split over bits [3:0] and [15:14] of the immediate
-  constexpr int kInFlight = (STAGES - 2) * 2 * kLoadsPerWave;  // loads that may stay outstanding
-  constexpr int kWaitStage = 0x0F70 | (kInFlight & 15) | ((kInFlight >> 4) << 14);
-
-#pragma unroll
-  for (int st = 0; st < STAGES; ++st) {
-    issue_x(st, st * BK, st < k_steps);
-    issue_w(st, st * BK, st < k_steps);
-  }
-  {
-    constexpr int first = (STAGES - 1) * 2 * kLoadsPerWave;  // everything but stage 0 may be in flight
-    __builtin_amdgcn_s_waitcnt(0x0F70 | (first & 15) | ((first >> 4) << 14));
-  }
-  __syncthreads();
-  read_frags(smem, 0, 0);
-
-  int slot_cur = 0;
-  for (int kt = 0; kt < k_steps; ++kt) {
-    const int slot_next = slot_cur + 1 == STAGES ? 0 : slot_cur + 1;
-    const char* st = smem + slot_cur * kStageBytes;
-    const char* nx = smem + slot_next * kStageBytes;
-#pragma unroll
-    for (int ks = 0; ks < KS - 1; ++ks) {
-      read_frags(st, ks + 1, (ks + 1) & 1);
-      mma(ks & 1);
-#pragma unroll
-      for (int q = 0; q < 8; ++q) {
-        __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);  // 2 MFMA
-        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // 1 DS read
-      }
-    }
-    __builtin_amdgcn_s_waitcnt(kWaitStage);  // this wave's loads of the next stage are in LDS
-    __syncthreads();                         // everyone's are; nobody reads stage slot_cur any more
-    const bool more = kt + STAGES < k_steps;
-    issue_x(slot_cur, (kt + STAGES) * BK, more);
-    issue_w(slot_cur, (kt + STAGES) * BK, more);
-    read_frags(nx, 0, 0);
-    mma((KS - 1) & 1);
-#pragma unroll
-    for (int q = 0; q < 8; ++q) {
-      __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
-      __builtin_amdgcn_sched_group_barrier(0x020, kLoadsPerWave / 4, 0);  // VMEM reads
-      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-    }
-    slot_cur = slot_next;
-  }
-  __builtin_amdgcn_s_waitcnt(0x0F70);  // drain the (empty) trailing loads before LDS goes away
-
-  // ---- epilogue.  acc[i][j] is the 32x32 block (weight fragment i) x (activation fragment j);
-  // lane l holds activation row j*32 + l%32 and, for g = 0..3, the 4 consecutive weight
-  // rows i*32 + 8g + 4*(l/32) + 0..3  -> 4 consecutive output columns.
-  const int half = lane >> 5;
-#pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    const int row = row0 + wm * 128 + j * 32 + (lane & 31);
-    if (row >= row_end) continue;
-    uint16_t* crow = a.C + (size_t)row * a.n_out;
-    if (EPI == EPI_SWIGLU) {
-#pragma unroll
-      for (int q = 0; q < 2; ++q)
-#pragma unroll
-        for (int g = 0; g < 4; ++g) {
-          const int col = n0 + wn * 64 + q * 32 + 8 * g + 4 * half;
-          uint16_t o[4];
-#pragma unroll
-          for (int r = 0; r < 4; ++r)
-            o[r] = lz::f32_to_bf16(silu(acc[2 * q][j][4 * g + r]) * acc[2 * q + 1][j][4 * g + r]);
-          uint2 pk;
-          pk.x = uint32_t(o[0]) | (uint32_t(o[1]) << 16);
-          pk.y = uint32_t(o[2]) | (uint32_t(o[3]) << 16);
-          *(uint2*)(crow + col) = pk;
-        }
-    } else {
-#pragma unroll
-      for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int g = 0; g < 4; ++g) {
-          const int col = n0 + wn * 128 + i * 32 + 8 * g + 4 * half;
-          uint16_t o[4];
-#pragma unroll
-          for (int r = 0; r < 4; ++r) {
-            float v = acc[i][j][4 * g + r];
-            if (EPI == EPI_GELU) v = gelu_exact(v);
-            o[r] = lz::f32_to_bf16(v);
-          }
-          uint2 pk;
-          pk.x = uint32_t(o[0]) | (uint32_t(o[1]) << 16);
-          pk.y = uint32_t(o[2]) | (uint32_t(o[3]) << 16);
-          *(uint2*)(crow + col) = pk;
-        }
-    }
-  }
+  const int rows = row_end - row0;  // > 0; more than 256 means a full tile
+  if (rows > 192) gemm_tile<EPI, 4>(a, smem, slot, row0, row_end, n0);
+  else if (rows > 128) gemm_tile<EPI, 3>(a, smem, slot, row0, row_end, n0);
+  else if (rows > 64) gemm_tile<EPI, 2>(a, smem, slot, row0, row_end, n0);
+  else gemm_tile<EPI, 1>(a, smem, slot, row0, row_end, n0);
 #endif
 }
 
 template <int EPI>
 int32_t launch_mfma(const MfmaArgs& a, hipStream_t st) {
-  // LZ_GEMM_VARIANT: 0 (default) = 64-wide stages in a 2-deep ring; 1 = 32-wide stages, 4-deep
-  static const int variant = [] { const char* e = getenv("LZ_GEMM_VARIANT"); return e ? atoi(e) : 0; }();
-  void (*kern)(MfmaArgs) = variant == 1 ? gemm_mfma_kernel<EPI, 32, 4> : gemm_mfma_kernel<EPI, 64, 2>;
-  const int lds_bytes = 128 * 1024;
+  void (*kern)(MfmaArgs) = gemm_mfma_kernel<EPI>;
   static bool configured = false;  // per-process attribute; idempotent, so a benign race at worst
   if (!configured) {
-    if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes) !=
+    if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes) !=
         hipSuccess)
       return LZ_EHIP;
     configured = true;
   }
   const long long units = (long long)(a.t.capacity / kGroupM) * ((a.n_tiles + kGroupN - 1) / kGroupN);
   const long long per_xcd = (units + 7) / 8;
-  hipLaunchKernelGGL(kern, dim3((unsigned)(per_xcd * kGroupM * kGroupN * 8)), dim3(256), lds_bytes, st, a);
+  hipLaunchKernelGGL(kern, dim3((unsigned)(per_xcd * kGroupM * kGroupN * 8)), dim3(256), kLdsBytes, st, a);
   return lz::launch_status();
 }
 

@@ -220,8 +220,10 @@ def test_expert_ffn_bf16_generic_odd_shape(act):
                                        ("gelu", 512, 512)])
 def test_expert_ffn_bf16_mfma_ragged(act, d, ffn):
     cfg = scaled(CONFIGS["c1_tiny"], act=act, dtype="bf16", T=700, k=2, d=d, ffn=ffn, N=4, c=2)
-    # several row tiles, a tile boundary +1, an empty slot, a one-row slot, a ragged tail
+    # several row tiles, a tile boundary +1, an empty slot, a one-row slot, ragged tails
     assert _ffn_case(cfg, [257, 0, 1, 512, 300, 255, 74, 1], 3) <= 2e-2
+    # tails in every 64-row class (the kernel has one code path per class) and their edges
+    assert _ffn_case(cfg, [130, 190, 65, 128, 64, 193, 400, 230], 4) <= 2e-2
 
 
 def test_expert_ffn_clips_bad_offsets():
