@@ -5,7 +5,8 @@
  *
  * One pass of the layer is five device calls on one stream
  *
- *     lz_route -> lz_plan_dispatch -> lz_permute -> lz_expert_ffn -> lz_unpermute_combine
+ *     lz_route -> lz_plan_dispatch -> lz_permute (or lz_permute_scatter) -> lz_expert_ffn
+ *              -> lz_unpermute_combine
  *
  * plus host-side planning (allocation, placement, re-planning after rank loss).  The N
  * logical ranks of a placement plan live in one GPU's memory; no call communicates.
@@ -123,6 +124,13 @@ int32_t lz_plan_dispatch(const int32_t* topk_ids, const lz_shape* shape,
  * zero-filled.  x dev [T,d], xp dev [P,d], both of shape->dtype. */
 int32_t lz_permute(const void* x, const int32_t* row_to_pair, const lz_shape* shape,
                    void* xp, void* stream);
+
+/* The same reshuffle driven by the inverse map, token-major: xp[pair_to_row[t*k+kk], :] = x[t, :]
+ * for every pair whose row lies in [0,P).  x is read once and written k times (the compulsory
+ * traffic); rows of xp that no pair maps to are left untouched (they lie outside every slot
+ * range, so lz_expert_ffn never reads them).  Same buffers and dtypes as lz_permute. */
+int32_t lz_permute_scatter(const void* x, const int32_t* pair_to_row, const lz_shape* shape,
+                           void* xp, void* stream);
 
 /* Expert FFN over the permuted buffer (Sec. 2.1: experts are parallel FFNs; each replica
  * processes the tokens dispatched to it).  Rows [slot_offsets[s], slot_offsets[s+1]) use

@@ -10,7 +10,7 @@ import numpy as np
 __all__ = [
     "LZ_F32", "LZ_BF16", "LZ_GELU", "LZ_SWIGLU", "LzError", "Shape", "lib", "lib_path",
     "lz_strerror", "lz_version", "lz_plan_workspace_bytes", "lz_ffn_workspace_bytes",
-    "lz_route", "lz_plan_dispatch", "lz_permute", "lz_expert_ffn", "lz_unpermute_combine",
+    "lz_route", "lz_plan_dispatch", "lz_permute", "lz_permute_scatter", "lz_expert_ffn", "lz_unpermute_combine",
     "lz_ffn_tiles", "lz_ffn_up", "lz_ffn_down", "lz_allocate_replicas", "lz_place_mro", "lz_place_spread", "lz_recovery_probability",
     "lz_replan", "lz_apply_transfers", "MoELayer",
 ]
@@ -85,6 +85,7 @@ def _load():
         "lz_route": (i32, [vp, i32, i32, i32, vp, vp, vp]),
         "lz_plan_dispatch": (i32, [vp, sp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, u64, vp]),
         "lz_permute": (i32, [vp, vp, sp, vp, vp]),
+        "lz_permute_scatter": (i32, [vp, vp, sp, vp, vp]),
         "lz_expert_ffn": (i32, [vp, vp, vp, vp, sp, vp, vp, u64, vp]),
         "lz_unpermute_combine": (i32, [vp, vp, vp, sp, vp, vp]),
         "lz_ffn_tiles": (i32, [vp, sp, vp, u64, vp]),
@@ -159,6 +160,11 @@ def lz_plan_dispatch(topk_ids, shape, rank_tok_off, slot_expert, slot_counts, sl
 def lz_permute(x, row_to_pair, shape, xp, stream=None):
     _check(lib.lz_permute(_ptr(x), _ptr(row_to_pair), C.byref(shape.c_struct()), _ptr(xp),
                           _stream() if stream is None else stream), "lz_permute")
+
+
+def lz_permute_scatter(x, pair_to_row, shape, xp, stream=None):
+    _check(lib.lz_permute_scatter(_ptr(x), _ptr(pair_to_row), C.byref(shape.c_struct()), _ptr(xp),
+                                  _stream() if stream is None else stream), "lz_permute_scatter")
 
 
 def lz_expert_ffn(xp, slot_offsets, w1, w2, shape, yp, ws, ws_bytes, stream=None):
@@ -331,7 +337,7 @@ class MoELayer:
                          self.status, self.plan_ws, self.plan_ws_bytes)
 
     def permute(self, x):
-        lz_permute(x, self.row_to_pair, self.shape, self.xp)
+        lz_permute_scatter(x, self.pair_to_row, self.shape, self.xp)
 
     def expert_ffn(self):
         lz_expert_ffn(self.xp, self.slot_offsets, self.w1, self.w2, self.shape, self.yp, self.ffn_ws,

@@ -54,6 +54,64 @@ __global__ __launch_bounds__(256) void permute_elem_kernel(const Elem* __restric
   for (int v = lane; v < d; v += lz::kWave) xp[(size_t)row * d + v] = ok ? src[v] : Elem(0);
 }
 
+// Token-major form of the same reshuffle: xp[pair_to_row[t*k+kk], :] = x[t, :] for every pair.
+// Each row of x is read once and written k times, which is exactly the compulsory traffic
+// (the row-major gather above re-reads x once per copy when the copies land on different XCDs).
+__global__ __launch_bounds__(256) void permute_scatter_kernel(const u32x4* __restrict__ x,
+                                                              const int32_t* __restrict__ pair_to_row,
+                                                              int T, int k, long long P, int vec_per_row,
+                                                              u32x4* __restrict__ xp) {
+  const int lane = threadIdx.x % lz::kWave;
+  const long long t = (long long)blockIdx.x * kRowsPerBlock + threadIdx.x / lz::kWave;
+  if (t >= T) return;
+  long long rows[lz::kMaxK];
+#pragma unroll
+  for (int kk = 0; kk < lz::kMaxK; ++kk) {
+    rows[kk] = -1;
+    if (kk < k) {
+      const int r = pair_to_row[t * k + kk];
+      rows[kk] = (r >= 0 && r < P) ? r : -1;
+    }
+  }
+  const u32x4* src = x + (size_t)t * vec_per_row;
+  int v = lane;
+  for (; v + 3 * lz::kWave < vec_per_row; v += 4 * lz::kWave) {
+    const u32x4 a = __builtin_nontemporal_load(src + v), b = __builtin_nontemporal_load(src + v + lz::kWave),
+                c = __builtin_nontemporal_load(src + v + 2 * lz::kWave),
+                d = __builtin_nontemporal_load(src + v + 3 * lz::kWave);
+#pragma unroll
+    for (int kk = 0; kk < lz::kMaxK; ++kk)
+      if (kk < k && rows[kk] >= 0) {
+        u32x4* dst = xp + (size_t)rows[kk] * vec_per_row + v;
+        __builtin_nontemporal_store(a, dst);
+        __builtin_nontemporal_store(b, dst + lz::kWave);
+        __builtin_nontemporal_store(c, dst + 2 * lz::kWave);
+        __builtin_nontemporal_store(d, dst + 3 * lz::kWave);
+      }
+  }
+  for (; v < vec_per_row; v += lz::kWave) {
+    const u32x4 a = __builtin_nontemporal_load(src + v);
+#pragma unroll
+    for (int kk = 0; kk < lz::kMaxK; ++kk)
+      if (kk < k && rows[kk] >= 0) __builtin_nontemporal_store(a, xp + (size_t)rows[kk] * vec_per_row + v);
+  }
+}
+
+template <typename Elem>
+__global__ __launch_bounds__(256) void permute_scatter_elem_kernel(const Elem* __restrict__ x,
+                                                                   const int32_t* __restrict__ pair_to_row,
+                                                                   int T, int k, long long P, int d,
+                                                                   Elem* __restrict__ xp) {
+  const int lane = threadIdx.x % lz::kWave;
+  const long long t = (long long)blockIdx.x * kRowsPerBlock + threadIdx.x / lz::kWave;
+  if (t >= T) return;
+  for (int kk = 0; kk < k; ++kk) {
+    const int r = pair_to_row[t * k + kk];
+    if (r < 0 || r >= P) continue;
+    for (int v = lane; v < d; v += lz::kWave) xp[(size_t)r * d + v] = x[(size_t)t * d + v];
+  }
+}
+
 __device__ __forceinline__ void fma8(float* acc, const u32x4& v, float g) {
   const uint32_t w[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
@@ -149,6 +207,28 @@ extern "C" int32_t lz_permute(const void* x, const int32_t* row_to_pair, const l
   } else {
     hipLaunchKernelGGL(permute_elem_kernel<uint16_t>, dim3(blocks), dim3(256), 0, st,
                        (const uint16_t*)x, row_to_pair, P, shape->k, shape->d, (uint16_t*)xp);
+  }
+  return lz::launch_status();
+}
+
+extern "C" int32_t lz_permute_scatter(const void* x, const int32_t* pair_to_row, const lz_shape* shape,
+                                      void* xp, void* stream) {
+  if (!lz::shape_ok(shape)) return LZ_ESHAPE;
+  const long long P = (long long)shape->T * shape->k;
+  if (P == 0) return LZ_OK;
+  if (!x || !pair_to_row || !xp) return LZ_EINVAL;
+  hipStream_t st = (hipStream_t)stream;
+  const size_t row_bytes = (size_t)shape->d * lz::elem_bytes(shape->dtype);
+  const unsigned blocks = unsigned((shape->T + kRowsPerBlock - 1) / kRowsPerBlock);
+  if (row_bytes % 16 == 0 && aligned16(x) && aligned16(xp)) {
+    hipLaunchKernelGGL(permute_scatter_kernel, dim3(blocks), dim3(256), 0, st, (const u32x4*)x, pair_to_row,
+                       shape->T, shape->k, P, int(row_bytes / 16), (u32x4*)xp);
+  } else if (shape->dtype == LZ_F32) {
+    hipLaunchKernelGGL(permute_scatter_elem_kernel<float>, dim3(blocks), dim3(256), 0, st, (const float*)x,
+                       pair_to_row, shape->T, shape->k, P, shape->d, (float*)xp);
+  } else {
+    hipLaunchKernelGGL(permute_scatter_elem_kernel<uint16_t>, dim3(blocks), dim3(256), 0, st,
+                       (const uint16_t*)x, pair_to_row, shape->T, shape->k, P, shape->d, (uint16_t*)xp);
   }
   return lz::launch_status();
 }

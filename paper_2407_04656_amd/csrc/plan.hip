@@ -1,7 +1,7 @@
 // The flexible token dispatcher (Algorithm 1, Sec. 4.2) for all source ranks at once.
 //
 // Three kernels on one stream, no host synchronisation, no order-dependent atomics:
-//   count    each wave owns a chunk of <= 512 consecutive pairs of ONE source rank and
+//   count    each wave owns a chunk of <= 128 consecutive pairs of ONE source rank and
 //            histograms their expert ids with LDS atomics (counts commute)
 //   schedule one workgroup: scans the chunk histograms into per-(expert, rank) list
 //            positions, evaluates the algorithm's counts in exact integers, cuts every
@@ -13,7 +13,7 @@
 
 namespace {
 
-constexpr int kChunk = 512;          // pairs per wave-chunk
+constexpr int kChunk = 128;          // pairs per wave-chunk
 constexpr int kWavesPerBlock = 4;
 constexpr int kSchedThreads = 1024;
 
@@ -161,10 +161,25 @@ __global__ __launch_bounds__(kSchedThreads) void schedule_kernel(
   // ---- per (e, rank): list positions of the chunks, Tej, replica counts, slot order
   for (int idx = tid; idx < EN; idx += kSchedThreads) {
     const int e = idx / N, j = idx % N;
+    // exclusive scan of this (expert, rank)'s chunk counts, 8 independent loads at a time
+    const int32_t* __restrict__ cnt = t.chunkcnt;
+    int32_t* __restrict__ base = t.chunkbase;
     int running = 0;
-    for (int b = s_cf[j]; b < s_cf[j + 1]; ++b) {
-      t.chunkbase[(size_t)b * E + e] = running;
-      running += t.chunkcnt[(size_t)b * E + e];
+    int b = s_cf[j];
+    const int b_end = s_cf[j + 1];
+    for (; b + 8 <= b_end; b += 8) {
+      int v[8];
+#pragma unroll
+      for (int q = 0; q < 8; ++q) v[q] = cnt[(size_t)(b + q) * E + e];
+#pragma unroll
+      for (int q = 0; q < 8; ++q) {
+        base[(size_t)(b + q) * E + e] = running;
+        running += v[q];
+      }
+    }
+    for (; b < b_end; ++b) {
+      base[(size_t)b * E + e] = running;
+      running += cnt[(size_t)b * E + e];
     }
     t.Tej[idx] = running;
     if (Tej_opt) Tej_opt[idx] = running;

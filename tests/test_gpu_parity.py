@@ -160,6 +160,10 @@ def test_permute_and_combine(dtype, d):
     lz.lz_permute(to_dev(xh, bf16), to_dev(ref["row_to_pair"]), shape, xp)
     torch.cuda.synchronize()
     assert np.array_equal(to_host(xp), om.permute(xh, ref["row_to_pair"], k))      # a copy: bit exact
+    xp2 = torch.zeros((T * k, d), dtype=tdt, device=DEV)
+    lz.lz_permute_scatter(to_dev(xh, bf16), to_dev(ref["pair_to_row"]), shape, xp2)  # token-major form
+    torch.cuda.synchronize()
+    assert np.array_equal(to_host(xp2), om.permute(xh, ref["row_to_pair"], k))
     y = torch.empty((T, d), dtype=tdt, device=DEV)
     g32 = gates.astype(np.float32)
     lz.lz_unpermute_combine(xp, to_dev(ref["pair_to_row"]), to_dev(g32), shape, y)
