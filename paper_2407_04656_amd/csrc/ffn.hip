@@ -333,11 +333,15 @@ __device__ __forceinline__ void gemm_tile(const MfmaArgs& a, char* smem, int slo
     }
   };
   bf16x8 xf[2][XF], wf[2][4];
+  // read order = order of first use by the MFMAs (weight fragment 0, all activation fragments,
+  // weight fragments 1..3), so that with one read issued per two MFMAs every fragment lands
+  // at least ten MFMAs before it is needed
   auto read_frags = [&](const char* stage, int ks, int set) {
-#pragma unroll
-    for (int i = 0; i < 4; ++i) wf[set][i] = *(const bf16x8*)(stage + wbase + i * 32 * kRowBytes + fragoff[ks]);
+    wf[set][0] = *(const bf16x8*)(stage + wbase + fragoff[ks]);
 #pragma unroll
     for (int j = 0; j < XF; ++j) xf[set][j] = *(const bf16x8*)(stage + xbase + j * 32 * kRowBytes + fragoff[ks]);
+#pragma unroll
+    for (int i = 1; i < 4; ++i) wf[set][i] = *(const bf16x8*)(stage + wbase + i * 32 * kRowBytes + fragoff[ks]);
   };
   auto mma = [&](int set) {
 #pragma unroll
