@@ -65,6 +65,10 @@ class Shape:
 
 
 def lib_path() -> str:
+    """The in-tree library, or the build LAZARUS_MOE_LIB points at (same ABI, other build flags)."""
+    override = os.environ.get("LAZARUS_MOE_LIB")
+    if override:
+        return override
     return os.path.join(os.path.dirname(os.path.abspath(__file__)), "liblazarus_moe.so")
 
 

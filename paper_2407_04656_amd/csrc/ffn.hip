@@ -5,20 +5,21 @@
 //   GEMM-2   yp[P, d]       = hidden[P, ffn] * W2[slot]^T
 //
 // Group sizes are data dependent and only known on the device, so a one-workgroup kernel
-// first turns slot_offsets into a table of row tiles (slot, first row, end row); the GEMM
-// grid is sized for the worst case and surplus workgroups exit.
+// first turns slot_offsets into a table of row tiles (slot, first row, end row) and, for the
+// MFMA path, into one queue of work units per XCD.
 //
-// bf16 path (gfx950 MFMA): 256x256 workgroup tile, 4 waves in 2x2, each wave a 128x128
-// patch = 4x4 v_mfma_f32_32x32x16_bf16 accumulators (fp32, 256 AGPRs).  Both operands are
-// K-contiguous and are streamed HBM -> LDS with 16-byte buffer loads that write LDS
-// directly, through a ring of LDS stages (64 K-columns x 2 stages); fragment reads are
-// software pipelined over two register sets.  The XOR swizzle that keeps the ds_read_b128
-// fragment reads conflict-free is applied on the global-address side because a
-// direct-to-LDS load fixes the LDS side to lane order.  Buffer descriptors bound every load, so ragged tiles cannot fault.  The
-// MFMA takes the weight fragment as its row operand, which leaves each lane with 4
-// consecutive output columns per accumulator group: 8-byte bf16 stores, no LDS transpose.
-// For SwiGLU the weight tile interleaves 32-row fragments of Wg and Wu, so the gate and up
-// values of one output element sit in the same lane and register index.
+// bf16 path (gfx950 MFMA): persistent kernel, one workgroup per CU, drawing 256x256 tiles from
+// its XCD's queue.  4 waves in 2x2, each wave a 128x128 patch = 4x4
+// v_mfma_f32_32x32x16_bf16 accumulators (fp32, 256 AGPRs).  Both operands are K-contiguous
+// and are streamed HBM -> LDS with 16-byte buffer loads that write LDS directly, through two
+// LDS stages of 64 K-columns; fragment reads are software pipelined over two register sets.
+// The XOR swizzle that keeps the ds_read_b128 fragment reads conflict-free is applied on the
+// global-address side because a direct-to-LDS load fixes the LDS side to lane order.  Buffer
+// descriptors bound every load, so ragged tiles cannot fault.  The MFMA takes the weight
+// fragment as its row operand, which leaves each lane with 4 consecutive output columns per
+// accumulator group: 8-byte bf16 stores, no LDS transpose.  For SwiGLU the weight tile
+// interleaves 32-row fragments of Wg and Wu, so the gate and up values of one output element
+// sit in the same lane and register index.
 //
 // Generic path (fp32 tensors, or bf16 shapes the MFMA tiling does not divide): a plain
 // 64x64x16 LDS-tiled kernel with fp32 FMA accumulation and full bounds checks.
@@ -40,8 +41,12 @@ struct TileTable {
   int32_t* slot;
   int32_t* row0;
   int32_t* row_end;
+  int32_t* units[2];  // per GEMM (0 = up, 1 = down): 8 lists of unit_cap[g] work units, one list per XCD
+  int unit_cap[2];
   int capacity;
 };
+
+constexpr int kUnitCount = 16;  // header[kUnitCount + 16*g + x] = length of XCD x's unit list for GEMM g
 
 // Row tiles are listed slot after slot; with group > 1 every slot's list is padded (slot = -1)
 // to a multiple of `group`, so that a group of consecutive row tiles never spans two slots.
@@ -50,49 +55,103 @@ inline int tile_capacity(long long P, int S, int BM, int group) {
   return int((n + group - 1) / group * group);
 }
 
-inline size_t tile_table_bytes(long long P, int S, int BM, int group) {
-  return lz::align256(sizeof(int32_t) * (kTileHeader + 3 * (size_t)tile_capacity(P, S, BM, group)));
+// Room in one XCD's list of work units (a unit = one row group x kGroupN column tiles): twice
+// an eighth of the worst-case number of units, so that lists of equal cost but unequal length
+// normally fit as they are.
+inline int unit_capacity(int capacity, int group, int n_tiles) {
+  if (n_tiles <= 0) return 0;
+  const long long units = (long long)(capacity / group) * ((n_tiles + kGroupN - 1) / kGroupN);
+  return int((units + 7) / 8 * 2);
 }
 
-inline TileTable carve_tiles(void* base, long long P, int S, int BM, int group) {
+inline size_t tile_table_bytes(long long P, int S, int BM, int group, int n_up, int n_down) {
+  const int cap = tile_capacity(P, S, BM, group);
+  const size_t ints = kTileHeader + 3 * (size_t)cap +
+                      8 * ((size_t)unit_capacity(cap, group, n_up) + unit_capacity(cap, group, n_down));
+  return lz::align256(sizeof(int32_t) * ints);
+}
+
+inline TileTable carve_tiles(void* base, long long P, int S, int BM, int group, int n_up, int n_down) {
   TileTable t;
   t.capacity = tile_capacity(P, S, BM, group);
   t.header = (int32_t*)base;
   t.slot = t.header + kTileHeader;
   t.row0 = t.slot + t.capacity;
   t.row_end = t.row0 + t.capacity;
+  t.unit_cap[0] = unit_capacity(t.capacity, group, n_up);
+  t.unit_cap[1] = unit_capacity(t.capacity, group, n_down);
+  t.units[0] = t.row_end + t.capacity;
+  t.units[1] = t.units[0] + 8 * (size_t)t.unit_cap[0];
   return t;
 }
 
+__device__ __forceinline__ void clip_slot(const int32_t* slot_offsets, int s, long long P, long long* a,
+                                          long long* b) {
+  long long lo = slot_offsets[s], hi = slot_offsets[s + 1];
+  lo = lo < 0 ? 0 : (lo > P ? P : lo);
+  hi = hi < lo ? lo : (hi > P ? P : hi);
+  *a = lo;
+  *b = hi;
+}
+
 // slot_offsets -> row tiles.  Offsets are clipped to [0, P] and made non-decreasing.
+//
+// For the MFMA GEMMs (n_tiles_up/down > 0) the kernel also deals each GEMM's work units (one
+// row group x kGroupN column tiles) to the 8 XCDs' queues: in (row group, column group) order,
+// eight at a time, alternate eights in opposite directions.  The XCDs thus work on neighbouring
+// column groups of the same row group at the same time and share its activation panel in the
+// memory-side cache, and a regular pattern of large and small units (a narrow last column
+// group, say) does not pile the large ones on the same XCDs; what imbalance is left the GEMM
+// kernel evens out by itself.  (Dealing by estimated cost, least-loaded queue first, was
+// within 2 % of this and costs a serial pass over the units; dealing the full row groups
+// first and the ragged ones last measured 1-5 % slower.)
 __global__ __launch_bounds__(256) void build_tiles_kernel(const int32_t* __restrict__ slot_offsets,
                                                           int S, long long P, int BM, int group,
-                                                          TileTable t) {
+                                                          int n_tiles_up, int n_tiles_down, TileTable t) {
   __shared__ int s_first[lz::kMaxN * lz::kMaxC + 1];
   if (threadIdx.x == 0) {
     int running = 0;
     for (int s = 0; s < S; ++s) {
-      long long a = slot_offsets[s], b = slot_offsets[s + 1];
-      a = a < 0 ? 0 : (a > P ? P : a);
-      b = b < a ? a : (b > P ? P : b);
+      long long a, b;
+      clip_slot(slot_offsets, s, P, &a, &b);
       s_first[s] = running;
       const int tiles = int((b - a + BM - 1) / BM);
-      running += (tiles + group - 1) / group * group;
-      if (running > t.capacity) running = t.capacity;
+      int padded = (tiles + group - 1) / group * group;
+      if (running + padded > t.capacity) padded = t.capacity - running;  // cannot happen for clipped offsets
+      running += padded;
     }
     s_first[S] = running;
     t.header[0] = running;
+    for (int i = 40; i < 64; ++i) t.header[i] = 0;  // tile-queue tickets of the GEMM kernels
   }
   __syncthreads();
   for (int s = threadIdx.x; s < S; s += blockDim.x) {
-    long long a = slot_offsets[s], b = slot_offsets[s + 1];
-    a = a < 0 ? 0 : (a > P ? P : a);
-    b = b < a ? a : (b > P ? P : b);
+    long long a, b;
+    clip_slot(slot_offsets, s, P, &a, &b);
     for (int i = s_first[s]; i < s_first[s + 1]; ++i) {
       const long long r0 = a + (long long)(i - s_first[s]) * BM;
       t.slot[i] = r0 < b ? s : -1;  // -1: padding entry, no rows
       t.row0[i] = int(r0 < b ? r0 : b);
       t.row_end[i] = int(b);
+    }
+  }
+  // deal the units, in (row group, column group) order, to the XCD queues in rows of eight,
+  // alternate rows in opposite directions
+  const int n_groups = s_first[S] / group;
+  for (int which = 0; which < 2; ++which) {
+    const int nt = which == 0 ? n_tiles_up : n_tiles_down;
+    const int ncg = (nt + kGroupN - 1) / kGroupN;
+    const int n_units = n_groups * ncg;  // 0 on the generic path
+    const int cap = t.unit_cap[which];
+    for (int u = threadIdx.x; u < n_units; u += blockDim.x) {
+      const int row = u / 8, i = u % 8;
+      const int x = (row & 1) ? 7 - i : i;
+      if (row < cap) t.units[which][(size_t)x * cap + row] = u;  // n_units <= 4 * cap: always true
+    }
+    if (threadIdx.x < 8) {
+      const int rows = n_units / 8, rest = n_units % 8;
+      const int i = (rows & 1) ? 7 - (int)threadIdx.x : (int)threadIdx.x;  // position of this XCD in the last row
+      t.header[kUnitCount + 16 * which + threadIdx.x] = rows + (i < rest ? 1 : 0);
     }
   }
 }
@@ -187,8 +246,8 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(const Elem* __restric
 // ------------------------------------------------------------------------------------------
 constexpr int BM = 256, BN = 256, BK = 64;
 constexpr int kRowBytes = BK * 2;                  // one tile row of a stage in LDS: 128 B = 8 chunks of 16 B
-constexpr int kStageBytes = (BM + BN) * kRowBytes; // activation tile (up to 256 rows), then weight tile; 2 stages
-constexpr int kLdsBytes = 2 * kStageBytes;          // 128 KiB of the CU's 160 KiB
+constexpr int kStageBytes = (BM + BN) * kRowBytes; // activation tile (up to 256 rows), then weight tile
+constexpr int kLdsBytes = 2 * kStageBytes;         // two stages: 128 KiB of the CU's 160 KiB
 
 struct MfmaArgs {
   const uint16_t* A;    // [P, K]
@@ -200,6 +259,7 @@ struct MfmaArgs {
   int n_out;            // output columns
   int up_row0;          // SwiGLU: first row of the up projection inside a slot's W
   int n_tiles;          // column tiles per row tile
+  int which;            // 0 = GEMM-1, 1 = GEMM-2: which unit lists and tickets of the tile table
   TileTable t;
 };
 
@@ -227,14 +287,17 @@ __device__ __forceinline__ float gelu_fast(float v) {
 // the key row/2.
 __device__ __forceinline__ int swz(int row) { return (row >> 1) & 7; }
 
-// Scheduling hint for one 16-wide K slice: ND ds_reads spread evenly through NM MFMAs.
-template <int Q, int ND, int NM>
-__device__ __forceinline__ void sched_mfma_ds() {
-  if constexpr (Q < ND) {
-    constexpr int m = (NM * (Q + 1)) / ND - (NM * Q) / ND;
-    if constexpr (m > 0) __builtin_amdgcn_sched_group_barrier(0x008, m, 0);  // MFMA
-    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                        // DS read
-    sched_mfma_ds<Q + 1, ND, NM>();
+// Scheduling hint for one 16-wide K slice: per MFMA, the ds_reads and direct-to-LDS loads that
+// fall due when ND reads and NV loads are spread evenly over NM MFMAs.
+template <int Q, int ND, int NM, int NV>
+__device__ __forceinline__ void sched_slice() {
+  if constexpr (Q < NM) {
+    constexpr int v = (NV * (Q + 1)) / NM - (NV * Q) / NM;
+    constexpr int d = (ND * (Q + 1)) / NM - (ND * Q) / NM;
+    if constexpr (v > 0) __builtin_amdgcn_sched_group_barrier(0x020, v, 0);  // VMEM read
+    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                        // MFMA
+    if constexpr (d > 0) __builtin_amdgcn_sched_group_barrier(0x100, d, 0);  // DS read
+    sched_slice<Q + 1, ND, NM, NV>();
   }
 }
 
@@ -246,7 +309,11 @@ __device__ __forceinline__ void gemm_tile(const MfmaArgs& a, char* smem, int slo
   constexpr int KS = BK / 16;             // 16-wide MFMA slices per stage
   constexpr int kLoadsX = 2 * XF;         // 1-KiB wave loads per wave for the activation tile (8 rows each)
   constexpr int kLoadsW = 8;              // ... for the 256-row weight tile
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  // The empty asm keeps the per-lane address arithmetic below inside the tile: hoisted out of
+  // the caller's tile loop it would be carried in registers through the whole kernel and spill.
+  int tid = threadIdx.x;
+  asm volatile("" : "+v"(tid));
+  const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave >> 1, wn = wave & 1;
 
   // ---- buffer descriptors: out-of-range loads return zero instead of faulting
@@ -304,15 +371,20 @@ __device__ __forceinline__ void gemm_tile(const MfmaArgs& a, char* smem, int slo
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-  // ---- main loop: two LDS stages of 64 K-columns, the loads of step kt+2 issued as soon as
-  // stage kt is free, and two register sets of fragments alternating over the four 16-wide
-  // slices so that the ds_reads of the next slice are in flight while the MFMAs of the
-  // current one run.  One barrier per step, placed after the reads of the step's last slice
-  // have been issued: past it nobody reads the current stage any more, so the loads of step
-  // kt+2 can start into it, and the next stage (whose loads every wave has waited for before
-  // the barrier) can be read.
+  // ---- main loop: two LDS stages of 64 K-columns, and two register sets of fragments
+  // alternating over the four 16-wide slices so that the ds_reads of the next slice are in
+  // flight while the MFMAs of the current one run.  One barrier per step, placed after the
+  // reads of the step's last slice have been issued: past it nobody reads the current stage any
+  // more, so the loads of step kt+2 can start into it, and the next stage (whose loads every
+  // wave has waited for before the barrier) can be read.
+  //
+  // The loads of step kt+2 are not issued in one burst: the weight loads (they come from HBM;
+  // the activation panel is mostly an L2 hit) go out one per two MFMAs during the slice after
+  // barrier kt, the activation loads during slices 0 and 1 of step kt+1.  A wave that issues a
+  // burst stands still until the texture unit has accepted it, and the MFMA pipe with it.
   const int k_steps = a.K / BK;
-  auto issue_stage = [&](int stage, int step) {
+  constexpr int kLoads = kLoadsW + kLoadsX;
+  auto issue = [&](int stage, int step, int q0, int q1) {
     // a step past the end of K is "loaded" through a zero-length descriptor: no memory traffic
     const bool real = step < k_steps;
     const __amdgpu_buffer_rsrc_t ra = real ? rsrcA : rsrcNull;
@@ -320,22 +392,24 @@ __device__ __forceinline__ void gemm_tile(const MfmaArgs& a, char* smem, int slo
     char* sX = smem + stage * kStageBytes;
     char* sW = sX + BM * kRowBytes;
 #pragma unroll
-    for (int i = 0; i < kLoadsW; ++i) {
-      const int u = wave * kLoadsW + i;
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(rb, (__attribute__((address_space(3))) void*)(sW + u * 1024), 16,
-                                               voffW[i], step * BK * 2, 0, 0);
-    }
-#pragma unroll
-    for (int i = 0; i < kLoadsX; ++i) {
-      const int u = wave * kLoadsX + i;
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(ra, (__attribute__((address_space(3))) void*)(sX + u * 1024), 16,
-                                               voffX[i], step * BK * 2, 0, 0);
+    for (int q = q0; q < q1; ++q) {
+      if (q < kLoadsW) {
+        const int u = wave * kLoadsW + q;
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rb, (__attribute__((address_space(3))) void*)(sW + u * 1024), 16,
+                                                 voffW[q], step * BK * 2, 0, 0);
+      } else {
+        const int u = wave * kLoadsX + (q - kLoadsW);
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(ra, (__attribute__((address_space(3))) void*)(sX + u * 1024), 16,
+                                                 voffX[q - kLoadsW], step * BK * 2, 0, 0);
+      }
     }
   };
+  constexpr int kAfterBarrier = kLoadsW;                 // loads issued in the slice after the barrier,
+  constexpr int kSlice0 = (kLoads - kAfterBarrier) / 2;  // in slice 0 of the next step,
+  constexpr int kSlice1 = kLoads - kAfterBarrier - kSlice0;  // and in its slice 1
   bf16x8 xf[2][XF], wf[2][4];
   // read order = order of first use by the MFMAs (weight fragment 0, all activation fragments,
-  // weight fragments 1..3), so that with one read issued per two MFMAs every fragment lands
-  // at least ten MFMAs before it is needed
+  // weight fragments 1..3)
   auto read_frags = [&](const char* stage, int ks, int set) {
     wf[set][0] = *(const bf16x8*)(stage + wbase + fragoff[ks]);
 #pragma unroll
@@ -351,13 +425,10 @@ __device__ __forceinline__ void gemm_tile(const MfmaArgs& a, char* smem, int slo
         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[set][i], xf[set][j], acc[i][j], 0, 0, 0);
   };
 
-  issue_stage(0, 0);
-  issue_stage(1, 1);
-  {
-    // s_waitcnt with only vmcnt set (bits [3:0] and [15:14]): stage 1 may still be in flight
-    constexpr int n = kLoadsX + kLoadsW;
-    __builtin_amdgcn_s_waitcnt(0x0F70 | (n & 15) | ((n >> 4) << 14));
-  }
+  issue(0, 0, 0, kLoads);
+  issue(1, 1, 0, kAfterBarrier);
+  // s_waitcnt with only vmcnt set (bits [3:0] and [15:14]): stage 1's first loads may still be in flight
+  __builtin_amdgcn_s_waitcnt(0x0F70 | kAfterBarrier);
   __syncthreads();
   read_frags(smem, 0, 0);
 
@@ -365,22 +436,25 @@ __device__ __forceinline__ void gemm_tile(const MfmaArgs& a, char* smem, int slo
     const int cur = kt & 1;
     const char* st = smem + cur * kStageBytes;
     const char* nx = smem + (cur ^ 1) * kStageBytes;
-#pragma unroll
-    for (int ks = 0; ks < KS - 1; ++ks) {
-      read_frags(st, ks + 1, (ks + 1) & 1);
-      mma(ks & 1);
-      sched_mfma_ds<0, 4 + XF, 4 * XF>();
-    }
+    issue(cur ^ 1, kt + 1, kAfterBarrier, kAfterBarrier + kSlice0);
+    read_frags(st, 1, 1);
+    mma(0);
+    sched_slice<0, 4 + XF, 4 * XF, kSlice0>();
+    issue(cur ^ 1, kt + 1, kAfterBarrier + kSlice0, kLoads);
+    read_frags(st, 2, 0);
+    mma(1);
+    sched_slice<0, 4 + XF, 4 * XF, kSlice1>();
+    read_frags(st, 3, 1);
+    mma(0);
+    sched_slice<0, 4 + XF, 4 * XF, 0>();
     __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wave's loads of the next stage are in LDS
     __syncthreads();                     // everyone's are; nobody reads stage `cur` any more
-    issue_stage(cur, kt + 2);
+    issue(cur, kt + 2, 0, kAfterBarrier);
     read_frags(nx, 0, 0);
-    mma((KS - 1) & 1);
-    // all loads of the freed stage go out first: the last one to land gates the next barrier
-    __builtin_amdgcn_sched_group_barrier(0x020, kLoadsX + kLoadsW, 0);
-    sched_mfma_ds<0, 4 + XF, 4 * XF>();
+    mma(1);
+    sched_slice<0, 4 + XF, 4 * XF, kAfterBarrier>();
   }
-  __builtin_amdgcn_s_waitcnt(0x0F70);  // drain the (empty) trailing loads before LDS goes away
+  __builtin_amdgcn_s_waitcnt(0x0F70);  // drain the (empty) trailing loads before LDS is reused
 
   // ---- epilogue.  acc[i][j] is the 32x32 block (weight fragment i) x (activation fragment j);
   // lane l holds activation row j*32 + l%32 and, for g = 0..3, the 4 consecutive weight rows
@@ -428,39 +502,63 @@ __device__ __forceinline__ void gemm_tile(const MfmaArgs& a, char* smem, int slo
   }
 }
 
+[[maybe_unused]] constexpr int kTicket = 40;  // header[kTicket + 8*g + x]: next entry of XCD x's tile queue for GEMM g
+[[maybe_unused]] constexpr int kDone = 56;    // header[kDone + g]: workgroups of GEMM g's launch that have finished
+
+// Persistent kernel: one workgroup per CU.  Every XCD has a queue of tiles (its unit list, 32
+// tile slots per unit: kGroupM row tiles of one slot x kGroupN column tiles); a workgroup takes
+// the next slot of its own XCD's queue with an atomic ticket, and once that queue is empty
+// helps with the other XCDs' queues.  The 32 tiles an XCD works on at a time therefore share
+// their activation and weight panels through that XCD's L2, and each XCD drains its queue at
+// its own pace.  (The hardware hands the workgroups of an ordinary launch to the XCDs strictly
+// in order of their index: there an XCD whose tiles take longer holds back the workgroups
+// queued behind it for every other XCD, which costs 10-40 % on ragged plans.)
 template <int EPI>
 __global__ __launch_bounds__(256, 1) void gemm_mfma_kernel(MfmaArgs a) {
 #if defined(__HIP_DEVICE_COMPILE__)  // the host pass only needs the launch stub, not the gfx950 builtins
   extern __shared__ __attribute__((aligned(1024))) char smem[];
   constexpr int BN_OUT = EPI == EPI_SWIGLU ? BN / 2 : BN;
-
-  // ---- which tile.  Work is cut into units of kGroupM row tiles (one slot) x kGroupN column
-  // tiles = 32 tiles, one per CU of an XCD.  Workgroups are dealt round-robin to the 8 XCDs,
-  // so workgroup b belongs to XCD b % 8; units are dealt to the XCDs in the same way, in
-  // (row group, column group) order.  At any moment the chip therefore works on neighbouring
-  // column groups of the same few slots: a unit's weight panels are fetched by one XCD only
-  // and its activation panel is shared through that XCD's L2.
-  const int n_row_tiles = a.t.header[0];
+  constexpr int kUnitTiles = kGroupM * kGroupN;
+  const int xcd = blockIdx.x % 8;  // workgroups are dealt round-robin to the 8 XCDs
   const int n_col_groups = (a.n_tiles + kGroupN - 1) / kGroupN;
-  const long long units = (long long)(n_row_tiles / kGroupM) * n_col_groups;
-  const int xcd = blockIdx.x % 8;
-  const int in_xcd = blockIdx.x / 8;
-  const long long unit = (long long)(in_xcd / (kGroupM * kGroupN)) * 8 + xcd;
-  if (unit >= units) return;
-  const int within = in_xcd % (kGroupM * kGroupN);
-  const int nt = int(unit % n_col_groups) * kGroupN + within / kGroupM;
-  if (nt >= a.n_tiles) return;
-  const int row_tile = int(unit / n_col_groups) * kGroupM + within % kGroupM;
-  const int slot = a.t.slot[row_tile];
-  if (slot < 0) return;
-  const int row0 = a.t.row0[row_tile];
-  const int row_end = a.t.row_end[row_tile];
-  const int n0 = nt * BN_OUT;
-  const int rows = row_end - row0;  // > 0; more than 256 means a full tile
-  if (rows > 192) gemm_tile<EPI, 4>(a, smem, slot, row0, row_end, n0);
-  else if (rows > 128) gemm_tile<EPI, 3>(a, smem, slot, row0, row_end, n0);
-  else if (rows > 64) gemm_tile<EPI, 2>(a, smem, slot, row0, row_end, n0);
-  else gemm_tile<EPI, 1>(a, smem, slot, row0, row_end, n0);
+  int* const ticket = a.t.header + kTicket + 8 * a.which;
+  const int32_t* const count = a.t.header + kUnitCount + 16 * a.which;
+  for (int hop = 0; hop < 8; ++hop) {
+    const int q = (xcd + hop) % 8;
+    const int n_slots = count[q] * kUnitTiles;
+    const int32_t* const list = a.t.units[a.which] + (size_t)q * a.t.unit_cap[a.which];
+    for (;;) {
+      __syncthreads();  // the previous tile's fragment reads are done: LDS may be reused
+      if (threadIdx.x == 0) *(volatile int*)smem = atomicAdd(ticket + q, 1);
+      __syncthreads();
+      const int t = __builtin_amdgcn_readfirstlane(*(volatile int*)smem);
+      __syncthreads();
+      if (t >= n_slots) break;  // every workgroup draws one ticket past the end of every queue, no more
+      const int unit = list[t / kUnitTiles];
+      const int within = t % kUnitTiles;
+      const int nt = (unit % n_col_groups) * kGroupN + within / kGroupM;
+      if (nt >= a.n_tiles) continue;
+      const int row_tile = (unit / n_col_groups) * kGroupM + within % kGroupM;
+      const int slot = a.t.slot[row_tile];
+      if (slot < 0) continue;
+      const int row0 = a.t.row0[row_tile];
+      const int row_end = a.t.row_end[row_tile];
+      const int n0 = nt * BN_OUT;
+      const int rows = row_end - row0;  // > 0; more than 256 means a full tile
+      if (rows > 192) gemm_tile<EPI, 4>(a, smem, slot, row0, row_end, n0);
+      else if (rows > 128) gemm_tile<EPI, 3>(a, smem, slot, row0, row_end, n0);
+      else if (rows > 64) gemm_tile<EPI, 2>(a, smem, slot, row0, row_end, n0);
+      else gemm_tile<EPI, 1>(a, smem, slot, row0, row_end, n0);
+    }
+  }
+  // the last workgroup to finish leaves the tickets at zero for the next launch on this table
+  if (threadIdx.x == 0) {
+    int* const done = a.t.header + kDone + a.which;
+    if (atomicAdd(done, 1) == (int)gridDim.x - 1) {
+      for (int q = 0; q < 8; ++q) ticket[q] = 0;
+      *done = 0;
+    }
+  }
 #endif
 }
 
@@ -468,15 +566,19 @@ template <int EPI>
 int32_t launch_mfma(const MfmaArgs& a, hipStream_t st) {
   void (*kern)(MfmaArgs) = gemm_mfma_kernel<EPI>;
   static bool configured = false;  // per-process attribute; idempotent, so a benign race at worst
+  static int n_workgroups = 0;
   if (!configured) {
     if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes) !=
         hipSuccess)
       return LZ_EHIP;
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
+      return LZ_EHIP;
+    n_workgroups = cus >= 8 ? cus / 8 * 8 : 8;  // one per CU (the LDS a workgroup takes allows no more)
     configured = true;
   }
-  const long long units = (long long)(a.t.capacity / kGroupM) * ((a.n_tiles + kGroupN - 1) / kGroupN);
-  const long long per_xcd = (units + 7) / 8;
-  hipLaunchKernelGGL(kern, dim3((unsigned)(per_xcd * kGroupM * kGroupN * 8)), dim3(256), kLdsBytes, st, a);
+  hipLaunchKernelGGL(kern, dim3(n_workgroups), dim3(256), kLdsBytes, st, a);
   return lz::launch_status();
 }
 
@@ -492,7 +594,12 @@ struct FfnWorkspace {
   size_t total_bytes;
   int BMrows;
   int group;
+  int n_up, n_down;  // column tiles of the two MFMA GEMMs (0 on the generic path)
 };
+
+TileTable tiles_of(const FfnWorkspace& w, const lz_shape* s) {
+  return carve_tiles(w.tiles, (long long)s->T * s->k, s->N * s->c, w.BMrows, w.group, w.n_up, w.n_down);
+}
 
 FfnWorkspace carve_ffn(void* ws, const lz_shape* s) {
   FfnWorkspace w;
@@ -502,7 +609,9 @@ FfnWorkspace carve_ffn(void* ws, const lz_shape* s) {
   w.hidden = ws;
   w.tiles = (char*)ws + hidden_bytes;
   w.group = mfma_shape(s) ? kGroupM : 1;
-  w.total_bytes = hidden_bytes + tile_table_bytes(P, s->N * s->c, w.BMrows, w.group);
+  w.n_up = mfma_shape(s) ? s->ffn / (s->act == LZ_SWIGLU ? BN / 2 : BN) : 0;
+  w.n_down = mfma_shape(s) ? s->d / BN : 0;
+  w.total_bytes = hidden_bytes + tile_table_bytes(P, s->N * s->c, w.BMrows, w.group, w.n_up, w.n_down);
   return w;
 }
 
@@ -533,9 +642,9 @@ extern "C" int32_t lz_ffn_tiles(const int32_t* slot_offsets, const lz_shape* sha
   if (P == 0) return LZ_OK;
   if (!slot_offsets) return LZ_EINVAL;
   const int S = shape->N * shape->c;
-  TileTable t = carve_tiles(w.tiles, P, S, w.BMrows, w.group);
+  TileTable t = tiles_of(w, shape);
   hipLaunchKernelGGL(build_tiles_kernel, dim3(1), dim3(256), 0, (hipStream_t)stream, slot_offsets, S, P,
-                     w.BMrows, w.group, t);
+                     w.BMrows, w.group, w.n_up, w.n_down, t);
   return lz::launch_status();
 }
 
@@ -548,7 +657,7 @@ extern "C" int32_t lz_ffn_up(const void* xp, const void* w1, const lz_shape* sha
   if (P == 0) return LZ_OK;
   if (!xp || !w1) return LZ_EINVAL;
   hipStream_t st = (hipStream_t)stream;
-  TileTable t = carve_tiles(w.tiles, P, shape->N * shape->c, w.BMrows, w.group);
+  TileTable t = tiles_of(w, shape);
   const bool swiglu = shape->act == LZ_SWIGLU;
   const int n1 = shape->ffn * (swiglu ? 2 : 1);
   if (!mfma_shape(shape)) {
@@ -583,7 +692,8 @@ extern "C" int32_t lz_ffn_up(const void* xp, const void* w1, const lz_shape* sha
   g1.w_rows = n1;
   g1.n_out = shape->ffn;
   g1.up_row0 = swiglu ? shape->ffn : 0;
-  g1.n_tiles = shape->ffn / (swiglu ? BN / 2 : BN);
+  g1.n_tiles = w.n_up;
+  g1.which = 0;
   g1.t = t;
   return swiglu ? launch_mfma<EPI_SWIGLU>(g1, st) : launch_mfma<EPI_GELU>(g1, st);
 }
@@ -597,7 +707,7 @@ extern "C" int32_t lz_ffn_down(const void* w2, const lz_shape* shape, void* yp, 
   if (P == 0) return LZ_OK;
   if (!w2 || !yp) return LZ_EINVAL;
   hipStream_t st = (hipStream_t)stream;
-  TileTable t = carve_tiles(w.tiles, P, shape->N * shape->c, w.BMrows, w.group);
+  TileTable t = tiles_of(w, shape);
   if (!mfma_shape(shape)) {
     const dim3 grid((shape->d + 63) / 64, t.capacity);
     if (shape->dtype == LZ_F32)
@@ -619,7 +729,8 @@ extern "C" int32_t lz_ffn_down(const void* w2, const lz_shape* shape, void* yp, 
   g2.w_rows = shape->d;
   g2.n_out = shape->d;
   g2.up_row0 = 0;
-  g2.n_tiles = shape->d / BN;
+  g2.n_tiles = w.n_down;
+  g2.which = 1;
   g2.t = t;
   return launch_mfma<EPI_NONE>(g2, st);
 }
