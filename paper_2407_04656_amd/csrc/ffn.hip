@@ -281,6 +281,14 @@ __device__ __forceinline__ float gelu_fast(float v) {
   return 0.5f * v + 0.5f * fabsf(v) * erf_abs;    // 0.5 v (1 + sign(v) erf_abs)
 }
 
+// Two fp32 -> one dword of two bf16, round to nearest even (v_cvt_pk_bf16_f32 on gfx950).
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+  const f32x2 v = {lo, hi};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
+}
+
 // 16-byte chunk c of tile row r lives at chunk position c ^ swz(r) of its 128-byte LDS row.
 // LDS has 64 banks of 4 B, so a ds_read_b128 is served 16 lanes at a time: 16 consecutive
 // rows at one logical chunk must cover 16 distinct 16-byte bank groups (256 B = 2 rows), hence
@@ -471,13 +479,12 @@ __device__ __forceinline__ void gemm_tile(const MfmaArgs& a, char* smem, int slo
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
           const int col = n0 + wn * 64 + q * 32 + 8 * g + 4 * half;
-          uint16_t o[4];
+          float o[4];
 #pragma unroll
-          for (int r = 0; r < 4; ++r)
-            o[r] = lz::f32_to_bf16(silu_fast(acc[2 * q][j][4 * g + r]) * acc[2 * q + 1][j][4 * g + r]);
+          for (int r = 0; r < 4; ++r) o[r] = silu_fast(acc[2 * q][j][4 * g + r]) * acc[2 * q + 1][j][4 * g + r];
           uint2 pk;
-          pk.x = uint32_t(o[0]) | (uint32_t(o[1]) << 16);
-          pk.y = uint32_t(o[2]) | (uint32_t(o[3]) << 16);
+          pk.x = pack_bf16x2(o[0], o[1]);
+          pk.y = pack_bf16x2(o[2], o[3]);
           *(uint2*)(crow + col) = pk;
         }
     } else {
@@ -486,16 +493,15 @@ __device__ __forceinline__ void gemm_tile(const MfmaArgs& a, char* smem, int slo
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
           const int col = n0 + wn * 128 + i * 32 + 8 * g + 4 * half;
-          uint16_t o[4];
+          float o[4];
 #pragma unroll
           for (int r = 0; r < 4; ++r) {
-            float v = acc[i][j][4 * g + r];
-            if (EPI == EPI_GELU) v = gelu_fast(v);
-            o[r] = lz::f32_to_bf16(v);
+            o[r] = acc[i][j][4 * g + r];
+            if (EPI == EPI_GELU) o[r] = gelu_fast(o[r]);
           }
           uint2 pk;
-          pk.x = uint32_t(o[0]) | (uint32_t(o[1]) << 16);
-          pk.y = uint32_t(o[2]) | (uint32_t(o[3]) << 16);
+          pk.x = pack_bf16x2(o[0], o[1]);
+          pk.y = pack_bf16x2(o[2], o[3]);
           *(uint2*)(crow + col) = pk;
         }
     }
