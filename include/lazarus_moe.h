@@ -152,9 +152,13 @@ int32_t lz_expert_ffn(const void* xp, const int32_t* slot_offsets,
 
 /* The three stages of lz_expert_ffn as separate calls, for callers that want to time or
  * interleave them; lz_expert_ffn is exactly tiles -> up -> down on the same workspace.
- *   lz_ffn_tiles  turns slot_offsets into the row-tile table kept in ws
+ *   lz_ffn_tiles  turns slot_offsets into the row-tile table and work queues kept in ws
  *   lz_ffn_up     hidden = act(xp W1^T) per slot, hidden kept in ws        (needs tiles)
- *   lz_ffn_down   yp = hidden W2^T per slot                                (needs up)    */
+ *   lz_ffn_down   yp = hidden W2^T per slot                                (needs up)
+ * The MFMA GEMMs are persistent kernels that draw their tiles from queues in ws with atomic
+ * tickets and reset the tickets when they finish, so up / down may be repeated on one table,
+ * but a workspace serves one call at a time: calls on the same ws must be ordered (one
+ * stream, or events), never concurrent. */
 int32_t lz_ffn_tiles(const int32_t* slot_offsets, const lz_shape* shape, void* ws, size_t ws_bytes,
                      void* stream);
 int32_t lz_ffn_up(const void* xp, const void* w1, const lz_shape* shape, void* ws, size_t ws_bytes,
