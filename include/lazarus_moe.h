@@ -30,7 +30,7 @@
  *     word and never cause an out-of-bounds access.
  *   - All matrices are row-major and dense.  dtype LZ_BF16 tensors hold bfloat16 bit
  *     patterns; accumulation is always fp32.
- *   - Limits: 1 <= k <= min(E, 8), E <= 256, N <= 64, c <= 64, P = T*k < 2^31 / max(d, ffn).
+ *   - Limits: 1 <= k <= min(E, 8), E <= 256, N <= 64, c <= 64, P = T*k <= 2^30 (buffers may exceed 4 GiB).
  */
 #ifndef LAZARUS_MOE_H
 #define LAZARUS_MOE_H

@@ -324,9 +324,11 @@ __device__ __forceinline__ void gemm_tile(const MfmaArgs& a, char* smem, int slo
   const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave >> 1, wn = wave & 1;
 
-  // ---- buffer descriptors: out-of-range loads return zero instead of faulting
+  // ---- buffer descriptors: out-of-range loads return zero instead of faulting.  The activation
+  // descriptor covers just this tile's rows, so 32-bit offsets do however large P is.
+  const int n_rows = row_end - row0 < BM ? row_end - row0 : BM;
   const __amdgpu_buffer_rsrc_t rsrcA = __builtin_amdgcn_make_buffer_rsrc(
-      (void*)a.A, 0, (int)(uint32_t)((unsigned long long)a.P * a.K * 2), 0x00020000);
+      (void*)(a.A + (size_t)row0 * a.K), 0, (int)((uint32_t)n_rows * (uint32_t)a.K * 2u), 0x00020000);
   const __amdgpu_buffer_rsrc_t rsrcB = __builtin_amdgcn_make_buffer_rsrc(
       (void*)(a.W + (size_t)slot * a.w_rows * a.K), 0, (int)(uint32_t)((unsigned long long)a.w_rows * a.K * 2),
       0x00020000);
@@ -342,8 +344,7 @@ __device__ __forceinline__ void gemm_tile(const MfmaArgs& a, char* smem, int slo
   for (int i = 0; i < kLoadsX; ++i) {
     const int r = (wave * kLoadsX + i) * 8 + (lane >> 3);
     const int chunk = (lane & 7) ^ swz(r);
-    int ga = row0 + r;
-    ga = ga < row_end ? ga : row_end - 1;  // rows past the slot's end repeat its last row (never stored)
+    const int ga = r < n_rows ? r : n_rows - 1;  // rows past the tile's end repeat its last row (never stored)
     voffX[i] = (int)(((uint32_t)ga * (uint32_t)a.K + (uint32_t)chunk * 8u) * 2u);
   }
 #pragma unroll
@@ -591,6 +592,8 @@ int32_t launch_mfma(const MfmaArgs& a, hipStream_t st) {
 inline bool mfma_shape(const lz_shape* s) {
   if (s->dtype != LZ_BF16) return false;
   if (s->d % BN != 0 || s->ffn % 64 != 0) return false;
+  // one slot's weights and one 256-row activation tile are addressed with 32-bit byte offsets
+  if ((long long)s->d * s->ffn * 4 >= (1ll << 31)) return false;
   return s->ffn % (s->act == LZ_SWIGLU ? BN / 2 : BN) == 0;
 }
 

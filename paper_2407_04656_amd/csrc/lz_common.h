@@ -21,9 +21,7 @@ inline bool shape_ok(const lz_shape* s) {
   if (s->N < 1 || s->N > kMaxN || s->c < 1 || s->c > kMaxC) return false;
   if (s->dtype != LZ_F32 && s->dtype != LZ_BF16) return false;
   if (s->act != LZ_GELU && s->act != LZ_SWIGLU) return false;
-  const int64_t P = int64_t(s->T) * s->k;
-  const int64_t widest = s->d > s->ffn ? s->d : s->ffn;
-  if (P * widest >= (int64_t(1) << 31)) return false;
+  if (int64_t(s->T) * s->k > (int64_t(1) << 30)) return false;  // pair and row indices are int32
   return true;
 }
 

@@ -74,6 +74,35 @@ def test_full_config(name, n_random):
         _check_outputs(cfg, layer, inp, w, ids, gates, ref, n_random, seed=step)
 
 
+def test_activations_beyond_4gib():
+    """Maximum sizes: P*d*2 and P*ffn*2 exceed 4 GiB, so every 32-bit byte offset into the permuted
+    activations or the hidden buffer would wrap.  Dispatch bit-exact on all pairs; copies and
+    outputs checked on sampled tokens, among them those of the last rows of the buffers."""
+    from workloads.configs import scaled
+    cfg = scaled(CONFIGS["c2_mixtral"], name="large_p", T=532480, d=2048, ffn=2048, E=8, k=2, N=4, c=3,
+                 seed=11)
+    assert cfg.T * cfg.k * cfg.d * 2 > 2 ** 32 and cfg.T * cfg.k * cfg.ffn * 2 > 2 ** 32
+    w = expert_weights(cfg, threads=16)
+    inp = step_inputs(cfg, 0)
+    ids, gates = om.route(inp["logits"], cfg.k)
+    plan = oracle_plan(cfg, ids)
+    layer = run_layer(cfg, plan, inp, w)
+    ref = om.plan_dispatch(ids, inp["rank_tok_off"], plan, cfg.E, cfg.N, cfg.c)
+    check_dispatch_exact(cfg, layer, ids, ref)
+    P = cfg.T * cfg.k
+    rows = np.unique(np.concatenate([np.random.default_rng(0).choice(P, size=2048, replace=False),
+                                     np.arange(P - 600, P), np.arange(0, 600)]))
+    assert np.array_equal(to_host(layer.xp[torch.from_numpy(rows).to(DEV)]),
+                          inp["x"][ref["row_to_pair"][rows] // cfg.k])
+    toks = np.unique(np.concatenate([_sample_tokens(cfg, ref, 128, seed=0),
+                                     ref["row_to_pair"][np.arange(P - 300, P)] // cfg.k]))
+    y_ref = om.layer_output(inp["x"], ids, gates, w["w1"], w["w2"], cfg.act, tokens=toks)
+    y = to_host(layer.y[torch.from_numpy(toks).to(DEV)])
+    assert rel_err(y, y_ref) <= tolerance(cfg)
+    row_err = np.max(np.abs(om.widen(y) - y_ref), axis=1) / np.max(np.abs(y_ref), axis=1)
+    assert row_err.max() <= 2 * tolerance(cfg), row_err.max()
+
+
 def test_post_failure_replan():
     """Config 5: config 3's step-0 plan loses ranks 2 and 5; re-plan on 6 ranks x 8 slots, move the
     weights with the transfer list, and run the layer under the new plan."""
