@@ -387,10 +387,13 @@ __device__ __forceinline__ void gemm_tile(const MfmaArgs& a, char* smem, int slo
   // more, so the loads of step kt+2 can start into it, and the next stage (whose loads every
   // wave has waited for before the barrier) can be read.
   //
-  // The loads of step kt+2 are not issued in one burst: the weight loads (they come from HBM;
-  // the activation panel is mostly an L2 hit) go out one per two MFMAs during the slice after
-  // barrier kt, the activation loads during slices 0 and 1 of step kt+1.  A wave that issues a
-  // burst stands still until the texture unit has accepted it, and the MFMA pipe with it.
+  // The loads of step kt+2 are not issued in one burst: a wave that issues a burst stands still
+  // until the texture unit has accepted it, and the MFMA pipe with it.  Weight loads first
+  // (they come from HBM; the activation panel is mostly an L2 hit): six go out during the slice
+  // after barrier kt, the rest during slice 0 of step kt+1, none in slices 1 and 2, which
+  // leaves every load two slices to land before the wait at the end of step kt+1.  (Measured
+  // on three workloads: 6 + rest + 0 beats 8 + half + half by 2-11 %, and 4, 5, 7, 8, 10, 12 or
+  // all 16 after the barrier.)
   const int k_steps = a.K / BK;
   constexpr int kLoads = kLoadsW + kLoadsX;
   auto issue = [&](int stage, int step, int q0, int q1) {
@@ -413,9 +416,8 @@ __device__ __forceinline__ void gemm_tile(const MfmaArgs& a, char* smem, int slo
       }
     }
   };
-  constexpr int kAfterBarrier = kLoadsW;                 // loads issued in the slice after the barrier,
-  constexpr int kSlice0 = (kLoads - kAfterBarrier) / 2;  // in slice 0 of the next step,
-  constexpr int kSlice1 = kLoads - kAfterBarrier - kSlice0;  // and in its slice 1
+  constexpr int kAfterBarrier = 6;                 // loads issued in the slice after the barrier,
+  constexpr int kSlice0 = kLoads - kAfterBarrier;  // and in slice 0 of the next step
   bf16x8 xf[2][XF], wf[2][4];
   // read order = order of first use by the MFMAs (weight fragment 0, all activation fragments,
   // weight fragments 1..3)
@@ -445,14 +447,13 @@ __device__ __forceinline__ void gemm_tile(const MfmaArgs& a, char* smem, int slo
     const int cur = kt & 1;
     const char* st = smem + cur * kStageBytes;
     const char* nx = smem + (cur ^ 1) * kStageBytes;
-    issue(cur ^ 1, kt + 1, kAfterBarrier, kAfterBarrier + kSlice0);
+    issue(cur ^ 1, kt + 1, kAfterBarrier, kLoads);
     read_frags(st, 1, 1);
     mma(0);
     sched_slice<0, 4 + XF, 4 * XF, kSlice0>();
-    issue(cur ^ 1, kt + 1, kAfterBarrier + kSlice0, kLoads);
     read_frags(st, 2, 0);
     mma(1);
-    sched_slice<0, 4 + XF, 4 * XF, kSlice1>();
+    sched_slice<0, 4 + XF, 4 * XF, 0>();
     read_frags(st, 3, 1);
     mma(0);
     sched_slice<0, 4 + XF, 4 * XF, 0>();
