@@ -145,7 +145,7 @@ int32_t lz_permute_scatter(const void* x, const int32_t* pair_to_row, const lz_s
  * in fp32.  LZ_BF16 uses MFMA kernels when d % 256 == 0 and ffn % 128 == 0 (ffn % 256 for
  * GELU) and a generic tiled kernel otherwise; LZ_F32 always uses the generic kernel.
  * slot_offsets is read on the device only; offsets outside [0,P] are clipped.
- *   xp dev [P,d] (in), yp dev [P,d] (out), ws >= lz_ffn_workspace_bytes(shape). */
+ *   xp dev [P,d] (in), yp dev [P,d] (out, 16-byte aligned), ws >= lz_ffn_workspace_bytes(shape). */
 int32_t lz_expert_ffn(const void* xp, const int32_t* slot_offsets,
                       const void* w1, const void* w2, const lz_shape* shape,
                       void* yp, void* ws, size_t ws_bytes, void* stream);

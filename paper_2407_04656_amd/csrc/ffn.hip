@@ -295,16 +295,16 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
 // the key row/2.
 __device__ __forceinline__ int swz(int row) { return (row >> 1) & 7; }
 
-// Scheduling hint for one 16-wide K slice: per MFMA, the ds_reads and direct-to-LDS loads that
-// fall due when ND reads and NV loads are spread evenly over NM MFMAs.
+// Scheduling hint for one 16-wide K slice of NM MFMAs: the ND ds_reads go out one per MFMA from
+// the start of the slice (the next slice waits on them), the NV direct-to-LDS loads are spread
+// evenly over the slice.
 template <int Q, int ND, int NM, int NV>
 __device__ __forceinline__ void sched_slice() {
   if constexpr (Q < NM) {
     constexpr int v = (NV * (Q + 1)) / NM - (NV * Q) / NM;
-    constexpr int d = (ND * (Q + 1)) / NM - (ND * Q) / NM;
-    if constexpr (v > 0) __builtin_amdgcn_sched_group_barrier(0x020, v, 0);  // VMEM read
-    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                        // MFMA
-    if constexpr (d > 0) __builtin_amdgcn_sched_group_barrier(0x100, d, 0);  // DS read
+    if constexpr (v > 0) __builtin_amdgcn_sched_group_barrier(0x020, v, 0);       // VMEM read
+    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                             // MFMA
+    if constexpr (Q < ND) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);      // DS read
     sched_slice<Q + 1, ND, NM, NV>();
   }
 }
@@ -388,12 +388,12 @@ __device__ __forceinline__ void gemm_tile(const MfmaArgs& a, char* smem, int slo
   // wave has waited for before the barrier) can be read.
   //
   // The loads of step kt+2 are not issued in one burst: a wave that issues a burst stands still
-  // until the texture unit has accepted it, and the MFMA pipe with it.  Weight loads first
-  // (they come from HBM; the activation panel is mostly an L2 hit): six go out during the slice
-  // after barrier kt, the rest during slice 0 of step kt+1, none in slices 1 and 2, which
-  // leaves every load two slices to land before the wait at the end of step kt+1.  (Measured
-  // on three workloads: 6 + rest + 0 beats 8 + half + half by 2-11 %, and 4, 5, 7, 8, 10, 12 or
-  // all 16 after the barrier.)
+  // until the texture unit has accepted it, and the MFMA pipe with it.  Six go out during the
+  // slice after barrier kt, the rest during slice 0 of step kt+1, none in slices 1 and 2, which
+  // leaves every load two slices to land before the wait at the end of step kt+1; the
+  // activation loads go first.  (Measured on three workloads: 6 + rest + 0 beats 8 + half + half
+  // by 2-11 %, and 4, 5, 7, 8, 10, 12 or all 16 after the barrier; activations first is 0.7 %
+  // ahead of weights first on the first GEMM and level on the second.)
   const int k_steps = a.K / BK;
   constexpr int kLoads = kLoadsW + kLoadsX;
   auto issue = [&](int stage, int step, int q0, int q1) {
@@ -405,14 +405,14 @@ __device__ __forceinline__ void gemm_tile(const MfmaArgs& a, char* smem, int slo
     char* sW = sX + BM * kRowBytes;
 #pragma unroll
     for (int q = q0; q < q1; ++q) {
-      if (q < kLoadsW) {
-        const int u = wave * kLoadsW + q;
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(rb, (__attribute__((address_space(3))) void*)(sW + u * 1024), 16,
-                                                 voffW[q], step * BK * 2, 0, 0);
-      } else {
-        const int u = wave * kLoadsX + (q - kLoadsW);
+      if (q < kLoadsX) {
+        const int u = wave * kLoadsX + q;
         __builtin_amdgcn_raw_ptr_buffer_load_lds(ra, (__attribute__((address_space(3))) void*)(sX + u * 1024), 16,
-                                                 voffX[q - kLoadsW], step * BK * 2, 0, 0);
+                                                 voffX[q], step * BK * 2, 0, 0);
+      } else {
+        const int u = wave * kLoadsW + (q - kLoadsX);
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rb, (__attribute__((address_space(3))) void*)(sW + u * 1024), 16,
+                                                 voffW[q - kLoadsX], step * BK * 2, 0, 0);
       }
     }
   };
@@ -468,33 +468,38 @@ __device__ __forceinline__ void gemm_tile(const MfmaArgs& a, char* smem, int slo
 
   // ---- epilogue.  acc[i][j] is the 32x32 block (weight fragment i) x (activation fragment j);
   // lane l holds activation row j*32 + l%32 and, for g = 0..3, the 4 consecutive weight rows
-  // i*32 + 8g + 4*(l/32) + 0..3  -> 4 consecutive output columns, one 8-byte bf16 store.
+  // i*32 + 8g + 4*(l/32) + 0..3  -> 4 consecutive output columns.  Stored straight from there,
+  // a wave store would touch 32 rows with 16 bytes each; such partial-line writes cost the
+  // second GEMM 10 % (timed with the stores removed).  So each 32-row fragment goes through a
+  // per-wave LDS patch (the stages are dead by now; LDS serves a wave's accesses in order) and
+  // leaves as 16 bytes per lane, whole 128-byte lines at a time.
+  constexpr int kWaveCols = EPI == EPI_SWIGLU ? 64 : 128;  // output columns of this wave
+  constexpr int kPitch = kWaveCols * 2 + 16;               // patch row in bytes: 16-byte aligned, rows 4 banks apart
+  constexpr int kLanesPerRow = kWaveCols / 8;              // 16-byte pieces of a patch row
+  constexpr int kRowsPerStore = 64 / kLanesPerRow;
+  char* const patch = smem + wave * (32 * kPitch);
   const int half = lane >> 5;
 #pragma unroll
   for (int j = 0; j < XF; ++j) {
-    const int row = row0 + wm * 32 * XF + j * 32 + (lane & 31);
-    if (row >= row_end) continue;
-    uint16_t* crow = a.C + (size_t)row * a.n_out;
+    char* const prow = patch + (lane & 31) * kPitch;
     if (EPI == EPI_SWIGLU) {
 #pragma unroll
       for (int q = 0; q < 2; ++q)
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
-          const int col = n0 + wn * 64 + q * 32 + 8 * g + 4 * half;
           float o[4];
 #pragma unroll
           for (int r = 0; r < 4; ++r) o[r] = silu_fast(acc[2 * q][j][4 * g + r]) * acc[2 * q + 1][j][4 * g + r];
           uint2 pk;
           pk.x = pack_bf16x2(o[0], o[1]);
           pk.y = pack_bf16x2(o[2], o[3]);
-          *(uint2*)(crow + col) = pk;
+          *(uint2*)(prow + (q * 32 + 8 * g + 4 * half) * 2) = pk;
         }
     } else {
 #pragma unroll
       for (int i = 0; i < 4; ++i)
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
-          const int col = n0 + wn * 128 + i * 32 + 8 * g + 4 * half;
           float o[4];
 #pragma unroll
           for (int r = 0; r < 4; ++r) {
@@ -504,9 +509,22 @@ __device__ __forceinline__ void gemm_tile(const MfmaArgs& a, char* smem, int slo
           uint2 pk;
           pk.x = pack_bf16x2(o[0], o[1]);
           pk.y = pack_bf16x2(o[2], o[3]);
-          *(uint2*)(crow + col) = pk;
+          *(uint2*)(prow + (i * 32 + 8 * g + 4 * half) * 2) = pk;
         }
     }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");  // keep the patch writes before the reads below
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+    for (int t = 0; t < 32 / kRowsPerStore; ++t) {
+      const int r = t * kRowsPerStore + lane / kLanesPerRow, piece = lane % kLanesPerRow;
+      const uint4 v = *(const uint4*)(patch + r * kPitch + piece * 16);
+      const int row = row0 + wm * 32 * XF + j * 32 + r;
+      if (row < row_end) *(uint4*)(a.C + (size_t)row * a.n_out + n0 + wn * kWaveCols + piece * 8) = v;
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");  // ... and the reads before the next fragment's writes
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
   }
 }
 
@@ -730,6 +748,7 @@ extern "C" int32_t lz_ffn_down(const void* w2, const lz_shape* shape, void* yp, 
                          (size_t)shape->d * shape->ffn, shape->d, 0, (uint16_t*)yp, t);
     return lz::launch_status();
   }
+  if ((uintptr_t)yp % 16 != 0) return LZ_EINVAL;  // the MFMA epilogue stores 16 bytes per lane
   MfmaArgs g2{};
   g2.A = (const uint16_t*)w.hidden;
   g2.W = (const uint16_t*)w2;
