@@ -40,7 +40,88 @@ def parse():
     ap.add_argument("--cpu-sample-tokens", type=int, default=0, help="0 = pick per workload")
     ap.add_argument("--copy-calib-mib", type=int, default=0,
                     help="also run a plain device copy of this many MiB (counter calibration for profiling)")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="skip the achievable-peak probes, the cold-cache bandwidth runs and the replan timing")
     return ap.parse_args()
+
+
+def achievable_peaks(torch, dev):
+    """What this machine reaches on a plain 1 GiB device copy and on a large square bf16 GEMM of the
+    vendor library: context for the fractions of the nominal peaks, not part of the path."""
+    n = 1 << 30
+    src = torch.empty(n, dtype=torch.uint8, device=dev).fill_(1)
+    dst = torch.empty_like(src)
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    for _ in range(2):
+        dst.copy_(src)
+    a.record()
+    for _ in range(10):
+        dst.copy_(src)
+    b.record()
+    torch.cuda.synchronize()
+    copy_gbs = 2.0 * n / (a.elapsed_time(b) / 10 * 1e-3) / 1e9
+    del src, dst
+    m = 8192
+    p = torch.randn((m, m), device=dev, dtype=torch.float32).to(torch.bfloat16)
+    q = torch.randn((m, m), device=dev, dtype=torch.float32).to(torch.bfloat16)
+    for _ in range(3):
+        torch.matmul(p, q.t())
+    a.record()
+    for _ in range(10):
+        torch.matmul(p, q.t())
+    b.record()
+    torch.cuda.synchronize()
+    tf = 2.0 * m ** 3 / (a.elapsed_time(b) / 10 * 1e-3) / 1e12
+    return {"device_copy_GBps": copy_gbs, "vendor_bf16_gemm_8192_TFLOPs": tf,
+            "note": "1 GiB torch copy (read + write bytes) and torch.matmul 8192^3 bf16 on this box"}
+
+
+def replan_latency(torch, lz, dev):
+    """Row a8 measured: config 5's scenario.  Config 3's step-0 plan loses two ranks; host time of
+    lz_replan (Eq. 1, MRO, greedy mapping, transfer list) and device time of lz_apply_transfers."""
+    from workloads import CONFIGS, expert_weights, step_inputs
+    cfg = CONFIGS["c5_postfailure"]
+    base = CONFIGS[cfg.base]
+    w = expert_weights(base, threads=16)
+    inp = step_inputs(base, 0, with_x=False)
+    shape_old, shape_new = lz.Shape.from_config(base), lz.Shape.from_config(cfg)
+    old = lz.MoELayer(shape_old, dev)
+    old.set_plan(np.zeros(shape_old.S, dtype=np.int32), inp["rank_tok_off"])
+    old.route(torch.from_numpy(inp["logits"]).to(dev))
+    torch.cuda.synchronize()
+    t_e = np.bincount(old.topk_ids.cpu().numpy().reshape(-1), minlength=base.E)
+    r = lz.lz_allocate_replicas(t_e, base.N, base.c, base.f)
+    old_plan = lz.lz_place_mro(r, t_e, base.N, base.c)
+    old.load_expert_weights(w["w1"], w["w2"], old_plan)
+    alive = np.ones(cfg.base_N, dtype=np.uint8)
+    alive[list(cfg.drop_ranks)] = 0
+    host = []
+    for _ in range(20):
+        t0 = time.perf_counter()
+        re = lz.lz_replan(old_plan, cfg.base_N, cfg.base_c, alive, t_e, cfg.c, cfg.f)
+        host.append((time.perf_counter() - t0) * 1e3)
+    n1 = w["w1"].shape[1]
+    w1n = torch.empty((shape_new.S, n1, cfg.d), dtype=torch.bfloat16, device=dev)
+    w2n = torch.empty((shape_new.S, cfg.d, cfg.ffn), dtype=torch.bfloat16, device=dev)
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    copy = []
+    for _ in range(5):
+        a.record()
+        lz.lz_apply_transfers(re["transfers"], old.w1, old.w2, shape_old.S, w1n, w2n, shape_new.S, shape_new)
+        b.record()
+        torch.cuda.synchronize()
+        copy.append(a.elapsed_time(b))
+    slot_bytes = (n1 * cfg.d + cfg.d * cfg.ffn) * 2
+    moved = len(re["transfers"]) * slot_bytes
+    out = {"scenario": f"{cfg.base} plan ({cfg.base_N}x{cfg.base_c} slots) loses ranks {list(cfg.drop_ranks)} "
+                       f"-> {cfg.N}x{cfg.c} slots",
+           "host_ms_median": float(np.median(host)), "host_ms_min": float(np.min(host)),
+           "copy_ms_median": float(np.median(copy)), "copy_ms_min": float(np.min(copy)),
+           "slots_copied": len(re["transfers"]), "remote_copies": int(sum(t[3] for t in re["transfers"])),
+           "copy_GBps": 2.0 * moved / (float(np.median(copy)) * 1e-3) / 1e9}
+    del old, w1n, w2n
+    torch.cuda.empty_cache()
+    return out
 
 
 def cpu_baseline(cfg, inp, w, plan_fn, n_tokens):
@@ -80,9 +161,6 @@ def main():
     from workloads import CONFIGS, expert_weights, step_inputs
 
     cfg = CONFIGS[args.workload]
-    if cfg.base is not None:
-        print("bench.py: post-failure workloads are covered by the GPU tests, pick c1..c4", file=sys.stderr)
-        sys.exit(2)
     dev = "cuda:0"
     torch.cuda.set_device(0)
     shape = lz.Shape.from_config(cfg)
@@ -90,7 +168,10 @@ def main():
 
     t_gen = time.perf_counter()
     inp = step_inputs(cfg, 0)
-    w = expert_weights(cfg, threads=16)
+    w = expert_weights(CONFIGS[cfg.base] if cfg.base else cfg, threads=16)
+    # multi-step workloads: fresh logits (a new popularity draw) every step, resident before timing
+    n_logits = min(cfg.steps, args.steps + args.warmup) if cfg.steps > 1 else 1
+    logits_host = [inp["logits"]] + [step_inputs(cfg, i, with_x=False)["logits"] for i in range(1, n_logits)]
     t_gen = time.perf_counter() - t_gen
 
     def to_dev(a, as_bf16=False):
@@ -99,27 +180,46 @@ def main():
             t = t.view(torch.bfloat16)
         return t.to(dev)
 
-    logits = to_dev(inp["logits"])
+    logits_all = [to_dev(l) for l in logits_host]
+    logits = logits_all[0]
     x = to_dev(inp["x"], bf16)
     layer = lz.MoELayer(shape, dev)
 
-    # plan from the realised step-0 routing (the paper's routing history): Eq. 1 + MRO, or
-    # the fixed allocation + spread placement of the tiny config -- all in the library
-    layer.set_plan(np.zeros(shape.S, dtype=np.int32), inp["rank_tok_off"])
-    layer.route(logits)
-    torch.cuda.synchronize()
-    t_e = np.bincount(layer.topk_ids.cpu().numpy().reshape(-1), minlength=cfg.E)
-
-    def lib_plan(t_e):
-        if cfg.replica_counts is not None:
-            r = np.array(cfg.replica_counts, dtype=np.int32)
+    def lib_plan(c, t_e):
+        if c.replica_counts is not None:
+            r = np.array(c.replica_counts, dtype=np.int32)
         else:
-            r = lz.lz_allocate_replicas(t_e, cfg.N, cfg.c, cfg.f)
-        if cfg.placement == "spread":
-            return lz.lz_place_spread(r, cfg.N, cfg.c)
-        return lz.lz_place_mro(r, t_e, cfg.N, cfg.c)
+            r = lz.lz_allocate_replicas(t_e, c.N, c.c, c.f)
+        if c.placement == "spread":
+            return lz.lz_place_spread(r, c.N, c.c)
+        return lz.lz_place_mro(r, t_e, c.N, c.c)
 
-    plan = lib_plan(t_e)
+    def routed_loads(c, logit_array):
+        probe = lz.MoELayer(lz.Shape.from_config(c), dev) if c is not cfg else layer
+        probe.set_plan(np.zeros(c.N * c.c, dtype=np.int32), rank_offsets(c))
+        probe.route(to_dev(logit_array))
+        torch.cuda.synchronize()
+        return np.bincount(probe.topk_ids.cpu().numpy().reshape(-1), minlength=c.E)
+
+    def rank_offsets(c):
+        return np.array([(i * c.T) // c.N for i in range(c.N + 1)], dtype=np.int32)
+
+    if cfg.base is None:
+        # plan from the realised step-0 routing (the paper's routing history): Eq. 1 + MRO, or
+        # the fixed allocation + spread placement of the tiny config -- all in the library
+        plan = lib_plan(cfg, routed_loads(cfg, inp["logits"]))
+        plan_note = "Eq.1 + MRO on step-0 loads" if cfg.replica_counts is None else "fixed counts, spread"
+    else:
+        # post-failure workload: the base config's step-0 plan loses ranks, lz_replan gives the new one
+        base = CONFIGS[cfg.base]
+        t_e = routed_loads(base, step_inputs(base, 0, with_x=False)["logits"])
+        alive = np.ones(cfg.base_N, dtype=np.uint8)
+        alive[list(cfg.drop_ranks)] = 0
+        plan = lz.lz_replan(lib_plan(base, t_e), cfg.base_N, cfg.base_c, alive, t_e, cfg.c, cfg.f)["new_slot_expert"]
+        plan_note = f"lz_replan of {cfg.base}'s plan after losing ranks {list(cfg.drop_ranks)}"
+    if cfg.steps > 1:
+        plan_note += f"; fresh logits each step ({n_logits} draws), plan kept"
+    torch.cuda.empty_cache()
     layer.set_plan(plan, inp["rank_tok_off"])
     layer.load_expert_weights(w["w1"], w["w2"], plan)
     torch.cuda.synchronize()
@@ -128,7 +228,7 @@ def main():
     ev = lambda: torch.cuda.Event(enable_timing=True)
     names = ["route", "plan", "permute", "ffn_up", "ffn_down", "combine"]
 
-    def step(marks=None):
+    def step(marks=None, logits=logits):
         s = layer
         if marks is not None:
             marks[0].record(stream)
@@ -160,8 +260,8 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    for _ in range(args.warmup):
-        step()
+    for i in range(args.warmup):
+        step(logits=logits_all[i % n_logits])
     torch.cuda.synchronize()
     assert int(layer.status.item()) == 0, "plan_dispatch flagged the plan"
 
@@ -169,7 +269,7 @@ def main():
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(args.steps):
-        step(marks[i])
+        step(marks[i], logits_all[(args.warmup + i) % n_logits])
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
 
@@ -187,8 +287,29 @@ def main():
 
     burst_ms = {"permute": burst(lambda: layer.permute(x)), "combine": burst(layer.unpermute_combine)}
 
+    # ... and cold: a 1 GiB fill between launches pushes x / yp out of L2 and the 256 MB memory-side cache
+    def cold(fn, n=8):
+        scratch = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+        a, b = ev(), ev()
+        ts = []
+        for i in range(n):
+            scratch.fill_(i)
+            a.record(stream)
+            fn()
+            b.record(stream)
+            torch.cuda.synchronize()
+            ts.append(a.elapsed_time(b))
+        del scratch
+        return float(np.median(ts))
+
+    cold_ms = None
+    if not args.no_extras:
+        cold_ms = {"permute": cold(lambda: layer.permute(x)), "combine": cold(layer.unpermute_combine)}
+
     ms_per_step = wall * 1e3 / args.steps
-    per = {n: float(np.mean([m[i].elapsed_time(m[i + 1]) for m in marks])) for i, n in enumerate(names)}
+    samples = {n: np.array([m[i].elapsed_time(m[i + 1]) for m in marks]) for i, n in enumerate(names)}
+    per = {n: float(np.mean(v)) for n, v in samples.items()}
+    step_ms = np.array([m[0].elapsed_time(m[6]) for m in marks])
     eb = 4 if cfg.dtype == "f32" else 2
     P, T, d, ffn, k = shape.P, shape.T, shape.d, shape.ffn, shape.k
     mult = 2 if cfg.act == "swiglu" else 1
@@ -229,9 +350,12 @@ def main():
         "data": "synthetic",
         "config": {"workload": cfg.name, "T": T, "d": d, "ffn": ffn, "E": shape.E, "k": k,
                    "N": shape.N, "c": shape.c, "act": cfg.act,
-                   "plan": "Eq.1 + MRO on step-0 loads" if cfg.replica_counts is None else "fixed counts, spread"},
+                   "plan": plan_note},
         "roofline": roofline,
         "kernels_ms": per,
+        "kernels_ms_median": {n: float(np.median(v)) for n, v in samples.items()},
+        "kernels_ms_min": {n: float(np.min(v)) for n, v in samples.items()},
+        "step_ms_by_events": {"median": float(np.median(step_ms)), "min": float(np.min(step_ms))},
         "derived": {
             "permute_GBps": gb_perm, "permute_frac_hbm": gb_perm / PEAK_HBM_GBS,
             "combine_GBps": gb_comb, "combine_frac_hbm": gb_comb / PEAK_HBM_GBS,
@@ -244,18 +368,36 @@ def main():
             "input_gen_s": t_gen,
         },
     }
+    if cold_ms is not None:
+        out["derived"]["permute_GBps_cold"] = permute_bytes / (cold_ms["permute"] * 1e-3) / 1e9
+        out["derived"]["combine_GBps_cold"] = combine_bytes / (cold_ms["combine"] * 1e-3) / 1e9
+    if not args.no_extras:
+        del layer, x
+        torch.cuda.empty_cache()
+        out["achievable"] = achievable_peaks(torch, dev)
+        if bf16:
+            out["roofline"]["frac_of_vendor_gemm"] = tf_up / out["achievable"]["vendor_bf16_gemm_8192_TFLOPs"]
+        out["replan"] = replan_latency(torch, lz, dev)
     if not args.no_cpu_baseline:
         n_cpu = args.cpu_sample_tokens or {"c1_tiny": 256, "c2_mixtral": 8192, "c3_gptmoe": 16384,
-                                           "c4_finegrained": 4096}.get(cfg.name, 256)
+                                           "c4_finegrained": 4096, "c5_postfailure": 16384}.get(cfg.name, 256)
 
         def oracle_plan(op, t_e):
-            if cfg.replica_counts is not None:
-                r = list(cfg.replica_counts)
-            else:
-                r = op.allocate_replicas(t_e, cfg.N, cfg.c, cfg.f)
-            if cfg.placement == "spread":
-                return np.array(op.place_spread(r, cfg.N, cfg.c))
-            return np.array(op.place_mro(r, t_e, cfg.N, cfg.c))
+            def eq1_placement(c, loads):
+                r = list(c.replica_counts) if c.replica_counts is not None else op.allocate_replicas(loads, c.N, c.c, c.f)
+                if c.placement == "spread":
+                    return np.array(op.place_spread(r, c.N, c.c))
+                return np.array(op.place_mro(r, loads, c.N, c.c))
+            if cfg.base is None:
+                return eq1_placement(cfg, t_e)
+            from oracle import moe_layer as om
+            base = CONFIGS[cfg.base]
+            ids0, _ = om.route(step_inputs(base, 0, with_x=False)["logits"], base.k)
+            loads0 = np.bincount(ids0.reshape(-1), minlength=base.E)
+            alive = np.ones(cfg.base_N, dtype=np.uint8)
+            alive[list(cfg.drop_ranks)] = 0
+            return np.array(op.replan(eq1_placement(base, loads0).tolist(), cfg.base_N, cfg.base_c, alive, loads0,
+                                      cfg.c, cfg.f)["new_slot_expert"])
 
         out["cpu_baseline"] = cpu_baseline(cfg, inp, w, oracle_plan, n_cpu)
     print(json.dumps(out), flush=True)
