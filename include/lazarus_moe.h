@@ -199,6 +199,12 @@ int32_t lz_place_mro(const int32_t* r_e, const int64_t* t_e, int32_t E, int32_t 
 int32_t lz_place_spread(const int32_t* r_e, int32_t E, int32_t N, int32_t c,
                         int32_t* slot_expert /* [N*c] out */);
 
+/* Compact baseline (Sec. 6.3): an expert's replicas on as few ranks as possible; replicas
+ * listed expert after expert fill rank after rank (q-th replica: rank q div c, local slot
+ * q mod c).  All pointers host. */
+int32_t lz_place_compact(const int32_t* r_e, int32_t E, int32_t N, int32_t c,
+                         int32_t* slot_expert /* [N*c] out */);
+
 /* Probability that n_alive uniformly drawn alive ranks still hold every expert, by
  * enumerating all C(N, n_alive) sets (Sec. 6.3; the objective of Theorem 1).  Writes the
  * count of recoverable sets and the total.  N <= 62.  All pointers host. */

@@ -129,6 +129,18 @@ def place_spread(r_e, N: int, c: int):
     return slot_expert
 
 
+def place_compact(r_e, N: int, c: int):
+    """Compact baseline (Sec. 6.3): an expert's replicas sit on as few ranks as possible.
+    Replicas listed expert after expert in id order fill rank after rank: the q-th replica
+    goes to rank q div c, local slot q mod c."""
+    if sum(int(v) for v in r_e) != N * c:
+        raise ValueError("replica counts must fill exactly N*c slots")
+    slot_expert = []
+    for e, cnt in enumerate(r_e):
+        slot_expert += [e] * int(cnt)
+    return slot_expert
+
+
 def recoverable(slot_expert, E: int, c: int, alive_ranks) -> bool:
     """Recovery needs every expert to keep a replica on some alive rank (Sec. 4.3)."""
     seen = set()

@@ -11,7 +11,7 @@ __all__ = [
     "LZ_F32", "LZ_BF16", "LZ_GELU", "LZ_SWIGLU", "LzError", "Shape", "lib", "lib_path",
     "lz_strerror", "lz_version", "lz_plan_workspace_bytes", "lz_ffn_workspace_bytes",
     "lz_route", "lz_plan_dispatch", "lz_permute", "lz_permute_scatter", "lz_expert_ffn", "lz_unpermute_combine",
-    "lz_ffn_tiles", "lz_ffn_up", "lz_ffn_down", "lz_allocate_replicas", "lz_place_mro", "lz_place_spread", "lz_recovery_probability",
+    "lz_ffn_tiles", "lz_ffn_up", "lz_ffn_down", "lz_allocate_replicas", "lz_place_mro", "lz_place_spread", "lz_place_compact", "lz_recovery_probability",
     "lz_replan", "lz_apply_transfers", "MoELayer",
 ]
 
@@ -98,6 +98,7 @@ def _load():
         "lz_allocate_replicas": (i32, [vp, i32, i32, i32, i32, vp]),
         "lz_place_mro": (i32, [vp, vp, i32, i32, i32, vp]),
         "lz_place_spread": (i32, [vp, i32, i32, i32, vp]),
+        "lz_place_compact": (i32, [vp, i32, i32, i32, vp]),
         "lz_recovery_probability": (i32, [vp, i32, i32, i32, i32, vp, vp]),
         "lz_replan": (i32, [vp, i32, i32, vp, vp, i32, i32, i32, vp, vp, vp, vp, vp]),
         "lz_apply_transfers": (i32, [vp, i32, vp, vp, i32, vp, vp, i32, sp, vp]),
@@ -225,6 +226,13 @@ def lz_place_spread(r_e, N, c):
     r = _i32(r_e)
     out = np.full(N * c, -1, dtype=np.int32)
     _check(lib.lz_place_spread(r.ctypes.data, len(r), N, c, out.ctypes.data), "lz_place_spread")
+    return out
+
+
+def lz_place_compact(r_e, N, c):
+    r = _i32(r_e)
+    out = np.full(N * c, -1, dtype=np.int32)
+    _check(lib.lz_place_compact(r.ctypes.data, len(r), N, c, out.ctypes.data), "lz_place_compact")
     return out
 
 

@@ -143,6 +143,16 @@ int32_t lz_place_spread(const int32_t* r_e, int32_t E, int32_t N, int32_t c, int
   return LZ_OK;
 }
 
+int32_t lz_place_compact(const int32_t* r_e, int32_t E, int32_t N, int32_t c, int32_t* slot_expert) {
+  int rc = check_counts(r_e, E, N, c);
+  if (rc != LZ_OK) return rc;
+  if (!slot_expert) return LZ_EINVAL;
+  int64_t q = 0;
+  for (int e = 0; e < E; ++e)
+    for (int n = 0; n < r_e[e]; ++n, ++q) slot_expert[q] = e;  // rank q / c, local slot q % c
+  return LZ_OK;
+}
+
 int32_t lz_recovery_probability(const int32_t* slot_expert, int32_t E, int32_t N, int32_t c,
                                 int32_t n_alive, uint64_t* n_recoverable, uint64_t* n_total) {
   if (!slot_expert || !n_recoverable || !n_total || E < 1 || N < 1 || N > 62 || c < 1 ||

@@ -40,6 +40,7 @@ def test_allocate_and_place_match_oracle():
         assert r.tolist() == op.allocate_replicas(t, N, c, f)
         assert lz.lz_place_mro(r, t, N, c).tolist() == op.place_mro(r, t, N, c)
         assert lz.lz_place_spread(r, N, c).tolist() == op.place_spread(r, N, c)
+        assert lz.lz_place_compact(r, N, c).tolist() == op.place_compact(r, N, c)
         n += 1
     assert n > 200
 
