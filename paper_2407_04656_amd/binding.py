@@ -78,6 +78,13 @@ def _load():
         raise ImportError(
             f"{path} is missing: build it first (python paper_2407_04656_amd/build.py or "
             "__graft_entry__.build()); there is no fallback path")
+    # PyTorch-ROCm ships its own HIP runtime.  Load it first when torch is installed, so that this
+    # library binds to the same runtime as the tensors and streams it is handed (with two
+    # runtimes in one process every launch on a torch stream fails).
+    try:
+        import torch  # noqa: F401
+    except ImportError:
+        pass
     L = C.CDLL(path)
     vp, i32, u64 = C.c_void_p, C.c_int32, C.c_size_t
     sp = C.POINTER(_Shape)

@@ -285,3 +285,27 @@ def test_layer_reduced_configs(name, T, d, ffn):
     assert np.array_equal(to_host(layer.xp), om.permute(inp["x"], ref["row_to_pair"], cfg.k))
     y_ref = om.layer_output(inp["x"], ids_ref, gates_ref, w["w1"], w["w2"], cfg.act)
     assert rel_err(to_host(layer.y), y_ref) <= tolerance(cfg)
+
+
+def test_padded_ep_reference_path_equals_flexible_dispatch():
+    """The padded traditional-EP reference path (equal replication, every slot padded to the
+    fullest one) and the flexible dispatcher run the same rows through the same experts: a row's
+    result does not depend on where its tile lies, so the two layer outputs are bit-identical,
+    and both match the fp64 definition.  The padded path moves more rows the more skewed the
+    loads are (Sec. 4.2, Sec. 6.5)."""
+    from paper_2407_04656_amd.load_ratio_sweep import run_ratio
+    from workloads import LayerConfig, ratio_logits
+    T, d, ffn, E, k, N, c = 4096, 256, 512, 8, 2, 8, 6
+    o = run_ratio(4, T=T, d=d, ffn=ffn, E=E, k=k, N=N, c=c, seed=7, dev=DEV, time_it=False)
+    assert torch.equal(o["y"].view(torch.int16), o["ep_y"].view(torch.int16))
+    cfg = LayerConfig(name="ratio4", T=T, d=d, ffn=ffn, E=E, k=k, N=N, c=c, dtype="bf16", act="swiglu", seed=7,
+                      bias="normal", bias_param=0.0)
+    w = expert_weights(cfg, threads=8)
+    x = step_inputs(cfg, 0)["x"]
+    ids, gates = om.route(ratio_logits(T, E, 4, 7), k)
+    toks = np.arange(0, T, 16)
+    y_ref = om.layer_output(x, ids, gates, w["w1"], w["w2"], "swiglu", tokens=toks)
+    assert rel_err(to_host(o["y"])[toks], y_ref) <= tolerance(cfg)
+    assert o["rank_rows_max"] <= 1.2 * o["rank_rows_mean"]           # flexible dispatch: ranks nearly level
+    assert o["ep_rank_rows"] >= 1.3 * o["rank_rows_mean"]            # padded EP: everyone pays for the fullest slot
+    assert o["ep_rows_total"] == N * c * o["ep_capacity"]

@@ -13,5 +13,6 @@ from .synth import (  # noqa: F401
     f32_to_bf16_bits,
     popularity_bias,
     rank_token_offsets,
+    ratio_logits,
     step_inputs,
 )

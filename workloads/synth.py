@@ -18,6 +18,7 @@ _STREAM_X = 12
 _STREAM_PERM = 13
 _STREAM_ZIPF_S = 14
 _STREAM_BIAS = 15
+_STREAM_RATIO = 16
 _STREAM_W1 = 21
 _STREAM_W2 = 22
 
@@ -80,6 +81,17 @@ def step_inputs(cfg: LayerConfig, step: int = 0, with_x: bool = True) -> dict:
         x = _rng(cfg.seed, _STREAM_X, step).standard_normal((cfg.T, cfg.d), dtype=np.float32)
         out["x"] = x if cfg.dtype == "f32" else f32_to_bf16_bits(x)
     return out
+
+
+def ratio_logits(T: int, E: int, ratio: float, seed: int) -> np.ndarray:
+    """Gating logits [T,E] fp32 whose expert popularity rises linearly from 1 (expert 0) to
+    `ratio` (expert E-1): logit = ln(popularity) + standard Gumbel noise, so that taking the
+    largest logits draws experts in proportion to their popularity (the single-layer
+    load-ratio workloads of the paper's ablation, most popular : least popular = ratio : 1)."""
+    pop = 1.0 + (float(ratio) - 1.0) * np.arange(E) / max(1, E - 1)
+    u = _rng(seed, _STREAM_RATIO, int(round(ratio * 1000))).random((T, E))
+    gumbel = -np.log(-np.log(np.clip(u, 1e-12, 1.0 - 1e-12)))
+    return (np.log(pop)[None, :] + gumbel).astype(np.float32)
 
 
 def _one_weight(cfg: LayerConfig, stream: int, e: int, shape) -> np.ndarray:
