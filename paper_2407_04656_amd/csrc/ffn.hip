@@ -109,15 +109,21 @@ __global__ __launch_bounds__(256) void build_tiles_kernel(const int32_t* __restr
                                                           int S, long long P, int BM, int group,
                                                           int n_tiles_up, int n_tiles_down, TileTable t) {
   __shared__ int s_first[lz::kMaxN * lz::kMaxC + 1];
+  // padded tile count of every slot (parallel: the offsets come from global memory), then one
+  // thread's running sum over LDS
+  for (int s = threadIdx.x; s < S; s += blockDim.x) {
+    long long a, b;
+    clip_slot(slot_offsets, s, P, &a, &b);
+    const int tiles = int((b - a + BM - 1) / BM);
+    s_first[s + 1] = (tiles + group - 1) / group * group;
+  }
+  __syncthreads();
   if (threadIdx.x == 0) {
     int running = 0;
     for (int s = 0; s < S; ++s) {
-      long long a, b;
-      clip_slot(slot_offsets, s, P, &a, &b);
-      s_first[s] = running;
-      const int tiles = int((b - a + BM - 1) / BM);
-      int padded = (tiles + group - 1) / group * group;
+      int padded = s_first[s + 1];
       if (running + padded > t.capacity) padded = t.capacity - running;  // cannot happen for clipped offsets
+      s_first[s] = running;
       running += padded;
     }
     s_first[S] = running;

@@ -1,11 +1,12 @@
 // The flexible token dispatcher (Algorithm 1, Sec. 4.2) for all source ranks at once.
 //
-// Three kernels on one stream, no host synchronisation, no order-dependent atomics:
+// Four kernels on one stream, no host synchronisation, no order-dependent atomics:
 //   count    each wave owns a chunk of <= 128 consecutive pairs of ONE source rank and
 //            histograms their expert ids with LDS atomics (counts commute)
-//   schedule one workgroup: scans the chunk histograms into per-(expert, rank) list
-//            positions, evaluates the algorithm's counts in exact integers, cuts every
-//            (expert, rank) receive list over that rank's replicas, scans the slot sizes
+//   schedule one workgroup per expert scans the chunk histograms into per-(expert, rank) list
+//            positions and evaluates the algorithm's counts in exact integers, in LDS; one
+//            more workgroup then cuts every (expert, rank) receive list over that rank's
+//            replicas and scans the slot sizes
 //   place    each wave revisits its chunk; a pair's position in its (expert, source rank)
 //            list is chunk base + ordered rank inside the chunk (wave ballots, one per
 //            distinct expert), which fixes destination rank, slot and row
@@ -16,6 +17,7 @@ namespace {
 constexpr int kChunk = 128;          // pairs per wave-chunk
 constexpr int kWavesPerBlock = 4;
 constexpr int kSchedThreads = 1024;
+constexpr int kExpertThreads = 256;
 
 struct PlanTables {
   // per chunk
@@ -30,6 +32,7 @@ struct PlanTables {
   int32_t* O;          // [E, N]  overflow
   int32_t* recv;       // [E, N]
   int32_t* ejstart;    // [E, N]  index of the first slot of e in rank j's sorted slot list
+  int32_t* estatus;    // [E]     status bits raised while scheduling expert e
   // per (expert, src, dst)
   int32_t* D;          // [E, N, N]
   int32_t* cumDst;     // [E, N, N+1] prefix of D over dst
@@ -63,6 +66,7 @@ PlanTables carve(void* ws, const lz_shape* s) {
   t.O = take(E * N);
   t.recv = take(E * N);
   t.ejstart = take(E * N);
+  t.estatus = take(E);
   t.D = take(E * N * N);
   t.cumDst = take(E * N * (N + 1));
   t.preSrc = take(E * N * N);
@@ -133,20 +137,132 @@ __global__ __launch_bounds__(256) void count_kernel(const int32_t* __restrict__ 
   if (lane == 0) t.chunkflag[b] = flag;
 }
 
-__global__ __launch_bounds__(kSchedThreads) void schedule_kernel(
+// Algorithm 1 for one expert per workgroup.  Everything an expert needs (N counts, N x N
+// assignments) lives in LDS between the phases, so the chain of dependent steps costs barriers,
+// not global-memory round trips; the tables the other kernels read are written out once.
+__global__ __launch_bounds__(kExpertThreads) void schedule_expert_kernel(
+    const int32_t* __restrict__ rank_tok_off, const int32_t* __restrict__ slot_expert, int T, int E,
+    int N, int c, int k, PlanTables t, int32_t* __restrict__ Tej_opt, int32_t* __restrict__ D_opt) {
+  __shared__ int s_off[lz::kMaxN + 1], s_cf[lz::kMaxN + 1];
+  __shared__ int s_R[lz::kMaxN], s_T[lz::kMaxN], s_L[lz::kMaxN], s_P[lz::kMaxN], s_O[lz::kMaxN];
+  __shared__ int s_D[lz::kMaxN * lz::kMaxN];
+  const int e = blockIdx.x;
+  const int tid = threadIdx.x, lane = tid % lz::kWave, w = tid / lz::kWave;
+  if (tid == 0) build_split(rank_tok_off, T, N, k, s_off, s_cf);
+  __syncthreads();
+
+  // ---- per source rank j (one wave each): positions of the chunks in the (e, j) list, T[e,j],
+  // the replicas of e on rank j and the index of their first slot in j's sorted slot list
+  for (int j = w; j < N; j += kExpertThreads / lz::kWave) {
+    const int b_end = s_cf[j + 1];
+    int running = 0;
+    for (int b0 = s_cf[j]; b0 < b_end; b0 += lz::kWave) {
+      const int b = b0 + lane;
+      const int v = b < b_end ? t.chunkcnt[(size_t)b * E + e] : 0;
+      int incl = v;
+#pragma unroll
+      for (int off = 1; off < lz::kWave; off <<= 1) {
+        const int n = __shfl_up(incl, off);
+        if (lane >= off) incl += n;
+      }
+      if (b < b_end) t.chunkbase[(size_t)b * E + e] = running + incl - v;
+      running += __shfl(incl, lz::kWave - 1);
+    }
+    int reps = 0, before = 0;
+    for (int l0 = 0; l0 < c; l0 += lz::kWave) {
+      const int l = l0 + lane;
+      const int se = l < c ? slot_expert[j * c + l] : -1;
+      reps += __popcll(__ballot(l < c && se == e));
+      before += __popcll(__ballot(l < c && se >= 0 && se < e));
+    }
+    if (lane == 0) {
+      const int idx = e * N + j;
+      s_T[j] = running;
+      s_R[j] = reps;
+      t.Tej[idx] = running;
+      if (Tej_opt) Tej_opt[idx] = running;
+      t.R[idx] = reps;
+      t.ejstart[idx] = before;
+    }
+  }
+  __syncthreads();
+
+  // ---- r_e, t_e (Algorithm 1, first two lines); capacity, local share, residual, overflow
+  long long re = 0, te = 0;
+  for (int j = 0; j < N; ++j) {
+    re += s_R[j];
+    te += s_T[j];
+  }
+  if (tid == 0) t.estatus[e] = (te > 0 && re == 0) ? LZ_PLAN_UNCOVERED_EXPERT : 0;
+  if (tid < N) {
+    const int j = tid;
+    long long lo = 0;
+    for (int j2 = 0; j2 < j; ++j2) lo += s_R[j2];
+    const long long hi = lo + s_R[j];
+    const int cap = re > 0 ? int((hi * te) / re - (lo * te) / re) : 0;
+    const int mine = s_T[j];
+    const int keep = cap < mine ? cap : mine;
+    s_L[j] = keep;
+    s_P[j] = cap - keep;
+    s_O[j] = mine - keep;
+    t.L[e * N + j] = keep;
+    t.Pres[e * N + j] = cap - keep;
+    t.O[e * N + j] = mine - keep;
+  }
+  __syncthreads();
+
+  // ---- D[e, i, :]: local share on the diagonal, overflow spread by residual capacity
+  if (tid < N) {
+    const int i = tid, idx = e * N + i;
+    long long tot = 0;
+    for (int j = 0; j < N; ++j) tot += s_P[j];
+    const long long o = s_O[i];
+    long long cumP = 0;
+    int cumD = 0;
+    int32_t* Drow = t.D + (size_t)idx * N;
+    int32_t* Crow = t.cumDst + (size_t)idx * (N + 1);
+    for (int j = 0; j < N; ++j) {
+      int dval;
+      if (j == i) {
+        dval = s_L[i];
+      } else {
+        const long long pj = s_P[j];
+        dval = (o > 0 && tot > 0) ? int((o * (cumP + pj)) / tot - (o * cumP) / tot) : 0;
+        cumP += pj;
+      }
+      s_D[i * N + j] = dval;
+      Drow[j] = dval;
+      if (D_opt) D_opt[(size_t)idx * N + j] = dval;
+      Crow[j] = cumD;
+      cumD += dval;
+    }
+    Crow[N] = cumD;
+  }
+  __syncthreads();
+
+  // ---- receive side: prefix over source ranks, recv[e, j]
+  if (tid < N) {
+    const int j = tid;
+    int running = 0;
+    for (int i = 0; i < N; ++i) {
+      t.preSrc[((size_t)(e * N + i)) * N + j] = running;
+      running += s_D[i * N + j];
+    }
+    t.recv[e * N + j] = running;
+  }
+}
+
+// Slot order inside every rank, slot sizes (balanced cut of the (e, j) receive list over its
+// R[e, j] slots), their exclusive scan, and the status word.  One workgroup.
+__global__ __launch_bounds__(kSchedThreads) void schedule_slots_kernel(
     const int32_t* __restrict__ rank_tok_off, const int32_t* __restrict__ slot_expert, int T, int E,
     int N, int c, int k, PlanTables t, int32_t* __restrict__ slot_counts,
-    int32_t* __restrict__ slot_offsets, int32_t* __restrict__ Tej_opt, int32_t* __restrict__ D_opt,
-    int32_t* __restrict__ status_opt) {
+    int32_t* __restrict__ slot_offsets, int32_t* __restrict__ status_opt) {
   __shared__ int s_off[lz::kMaxN + 1], s_cf[lz::kMaxN + 1];
-  __shared__ int s_re[lz::kMaxE], s_te[lz::kMaxE];
-  __shared__ long long s_tot[lz::kMaxE];
   __shared__ int s_status;
   __shared__ int s_scan[kSchedThreads];
   const int tid = threadIdx.x;
   const int S = N * c;
-  const int EN = E * N;
-
   if (tid == 0) {
     const bool bad = build_split(rank_tok_off, T, N, k, s_off, s_cf);
     s_status = bad ? LZ_PLAN_BAD_RANK_SPLIT : 0;
@@ -155,47 +271,14 @@ __global__ __launch_bounds__(kSchedThreads) void schedule_kernel(
   {
     int flag = 0;
     for (int b = tid; b < s_cf[N]; b += kSchedThreads) flag |= t.chunkflag[b];
+    for (int e = tid; e < E; e += kSchedThreads) flag |= t.estatus[e];
     if (flag) atomicOr(&s_status, flag);
-  }
-
-  // ---- per (e, rank): list positions of the chunks, Tej, replica counts, slot order
-  for (int idx = tid; idx < EN; idx += kSchedThreads) {
-    const int e = idx / N, j = idx % N;
-    // exclusive scan of this (expert, rank)'s chunk counts, 8 independent loads at a time
-    const int32_t* __restrict__ cnt = t.chunkcnt;
-    int32_t* __restrict__ base = t.chunkbase;
-    int running = 0;
-    int b = s_cf[j];
-    const int b_end = s_cf[j + 1];
-    for (; b + 8 <= b_end; b += 8) {
-      int v[8];
-#pragma unroll
-      for (int q = 0; q < 8; ++q) v[q] = cnt[(size_t)(b + q) * E + e];
-#pragma unroll
-      for (int q = 0; q < 8; ++q) {
-        base[(size_t)(b + q) * E + e] = running;
-        running += v[q];
-      }
-    }
-    for (; b < b_end; ++b) {
-      base[(size_t)b * E + e] = running;
-      running += cnt[(size_t)b * E + e];
-    }
-    t.Tej[idx] = running;
-    if (Tej_opt) Tej_opt[idx] = running;
-    int reps = 0, before = 0;
-    for (int l = 0; l < c; ++l) {
-      const int se = slot_expert[j * c + l];
-      reps += se == e;
-      before += se >= 0 && se < e;
-    }
-    t.R[idx] = reps;
-    t.ejstart[idx] = before;
   }
   for (int s = tid; s < S; s += kSchedThreads) {
     const int j = s / c;
     int se = slot_expert[s];
-    if (se < 0 || se >= E) {
+    const bool valid = se >= 0 && se < E;
+    if (!valid) {
       se = E;
       atomicOr(&s_status, LZ_PLAN_BAD_EXPERT_ID);
     }
@@ -208,92 +291,10 @@ __global__ __launch_bounds__(kSchedThreads) void schedule_kernel(
     }
     t.slot_pos[s] = pos;
     t.slot_sorted[j * c + pos] = s;
-  }
-  __syncthreads();
-
-  // ---- per expert: r_e, t_e (Algorithm 1, first two lines)
-  for (int e = tid; e < E; e += kSchedThreads) {
-    int re = 0, te = 0;
-    for (int j = 0; j < N; ++j) {
-      re += t.R[e * N + j];
-      te += t.Tej[e * N + j];
-    }
-    s_re[e] = re;
-    s_te[e] = te;
-    if (te > 0 && re == 0) atomicOr(&s_status, LZ_PLAN_UNCOVERED_EXPERT);
-  }
-  __syncthreads();
-
-  // ---- capacity, local share, residual, overflow
-  for (int idx = tid; idx < EN; idx += kSchedThreads) {
-    const int e = idx / N, j = idx % N;
-    long long lo = 0;
-    for (int j2 = 0; j2 < j; ++j2) lo += t.R[e * N + j2];
-    const long long hi = lo + t.R[idx];
-    const long long re = s_re[e], te = s_te[e];
-    const int cap = re > 0 ? int((hi * te) / re - (lo * te) / re) : 0;
-    const int mine = t.Tej[idx];
-    const int keep = cap < mine ? cap : mine;
-    t.L[idx] = keep;
-    t.Pres[idx] = cap - keep;
-    t.O[idx] = mine - keep;
-  }
-  __syncthreads();
-  for (int e = tid; e < E; e += kSchedThreads) {
-    long long tot = 0;
-    for (int j = 0; j < N; ++j) tot += t.Pres[e * N + j];
-    s_tot[e] = tot;
-  }
-  __syncthreads();
-
-  // ---- D[e, i, :]: local share on the diagonal, overflow spread by residual capacity
-  for (int idx = tid; idx < EN; idx += kSchedThreads) {
-    const int e = idx / N, i = idx % N;
-    const long long o = t.O[idx];
-    const long long tot = s_tot[e];
-    long long cumP = 0;
-    int cumD = 0;
-    int32_t* Drow = t.D + (size_t)idx * N;
-    int32_t* Crow = t.cumDst + (size_t)idx * (N + 1);
-    for (int j = 0; j < N; ++j) {
-      int dval;
-      if (j == i) {
-        dval = t.L[idx];
-      } else {
-        const long long pj = t.Pres[e * N + j];
-        dval = (o > 0 && tot > 0) ? int((o * (cumP + pj)) / tot - (o * cumP) / tot) : 0;
-        cumP += pj;
-      }
-      Drow[j] = dval;
-      if (D_opt) D_opt[(size_t)idx * N + j] = dval;
-      Crow[j] = cumD;
-      cumD += dval;
-    }
-    Crow[N] = cumD;
-  }
-  __syncthreads();
-
-  // ---- receive side: prefix over source ranks, recv[e, j]
-  for (int idx = tid; idx < EN; idx += kSchedThreads) {
-    const int e = idx / N, j = idx % N;
-    int running = 0;
-    for (int i = 0; i < N; ++i) {
-      const size_t at = ((size_t)(e * N + i)) * N + j;
-      t.preSrc[at] = running;
-      running += t.D[at];
-    }
-    t.recv[idx] = running;
-  }
-  __syncthreads();
-
-  // ---- slot sizes: balanced cut of the (e, j) receive list over its R[e, j] slots
-  for (int s = tid; s < S; s += kSchedThreads) {
-    const int j = s / c;
-    const int se = slot_expert[s];
     int cnt = 0;
-    if (se >= 0 && se < E) {
+    if (valid) {
       const int ej = se * N + j;
-      const long long m = t.slot_pos[s] - t.ejstart[ej];
+      const long long m = pos - t.ejstart[ej];
       const long long n = t.recv[ej], reps = t.R[ej];
       cnt = int(((m + 1) * n) / reps - (m * n) / reps);
     }
@@ -415,9 +416,11 @@ extern "C" int32_t lz_plan_dispatch(const int32_t* topk_ids, const lz_shape* sha
   if (P > 0)
     hipLaunchKernelGGL(count_kernel, dim3(blocks), dim3(256), 0, st, topk_ids, rank_tok_off, shape->T,
                        shape->E, shape->N, shape->k, t, row_to_pair);
-  hipLaunchKernelGGL(schedule_kernel, dim3(1), dim3(kSchedThreads), 0, st, rank_tok_off, slot_expert,
+  hipLaunchKernelGGL(schedule_expert_kernel, dim3(shape->E), dim3(kExpertThreads), 0, st, rank_tok_off,
+                     slot_expert, shape->T, shape->E, shape->N, shape->c, shape->k, t, Tej_opt, D_opt);
+  hipLaunchKernelGGL(schedule_slots_kernel, dim3(1), dim3(kSchedThreads), 0, st, rank_tok_off, slot_expert,
                      shape->T, shape->E, shape->N, shape->c, shape->k, t, slot_counts, slot_offsets,
-                     Tej_opt, D_opt, status_opt);
+                     status_opt);
   if (P > 0)
     hipLaunchKernelGGL(place_kernel, dim3(blocks), dim3(256), 0, st, topk_ids, rank_tok_off, shape->T,
                        shape->E, shape->N, shape->c, shape->k, t, slot_offsets, pair_to_row,
