@@ -1,8 +1,9 @@
 // Top-k gate routing (Sec. 2.1): for each token the k largest of E logits, descending,
 // ties towards the lower expert index, and the softmax over those k logits.
 //
-// A group of G = min(64, next_pow2(E)) lanes owns one token; each lane keeps up to
-// ceil(E/G) logits in registers.  One selection round is a max-reduction over the group of
+// A group of G = next_pow2(ceil(E/4)) <= 64 lanes owns one token; each lane keeps up to four
+// logits in registers (the per-lane maximum is plain ALU work, so few lanes per token mean few
+// shuffle steps and many tokens per wave).  One selection round is a max-reduction over the group of
 // a 64-bit key (order-preserving image of the logit in the high word, ~expert in the low
 // word), so the comparison and the tie rule are a single unsigned max.
 #include "lz_common.h"
@@ -101,12 +102,12 @@ extern "C" int32_t lz_route(const float* logits, int32_t T, int32_t E, int32_t k
   if (T == 0) return LZ_OK;
   if (!logits || !topk_ids || !topk_gates) return LZ_EINVAL;
   hipStream_t st = (hipStream_t)stream;
-  if (E <= 1) launch<1>(logits, T, E, k, topk_ids, topk_gates, st);
-  else if (E <= 2) launch<2>(logits, T, E, k, topk_ids, topk_gates, st);
-  else if (E <= 4) launch<4>(logits, T, E, k, topk_ids, topk_gates, st);
-  else if (E <= 8) launch<8>(logits, T, E, k, topk_ids, topk_gates, st);
-  else if (E <= 16) launch<16>(logits, T, E, k, topk_ids, topk_gates, st);
-  else if (E <= 32) launch<32>(logits, T, E, k, topk_ids, topk_gates, st);
+  if (E <= 4) launch<1>(logits, T, E, k, topk_ids, topk_gates, st);
+  else if (E <= 8) launch<2>(logits, T, E, k, topk_ids, topk_gates, st);
+  else if (E <= 16) launch<4>(logits, T, E, k, topk_ids, topk_gates, st);
+  else if (E <= 32) launch<8>(logits, T, E, k, topk_ids, topk_gates, st);
+  else if (E <= 64) launch<16>(logits, T, E, k, topk_ids, topk_gates, st);
+  else if (E <= 128) launch<32>(logits, T, E, k, topk_ids, topk_gates, st);
   else launch<64>(logits, T, E, k, topk_ids, topk_gates, st);
   return lz::launch_status();
 }
