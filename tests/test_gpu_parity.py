@@ -230,6 +230,40 @@ def test_expert_ffn_bf16_mfma_ragged(act, d, ffn):
     assert _ffn_case(cfg, [130, 190, 65, 128, 64, 193, 400, 230], 4) <= 2e-2
 
 
+def test_expert_ffn_stages_can_be_repeated_on_one_tile_table():
+    """The MFMA GEMMs draw their tiles from queues in the workspace with atomic tickets and
+    leave the tickets at zero when they finish: up / down repeated on one table (as a timing
+    loop does) must give the same bits as the first pass, also with many empty slots."""
+    cfg = scaled(CONFIGS["c1_tiny"], act="swiglu", dtype="bf16", T=1200, k=2, d=256, ffn=256, N=8, c=6)
+    S = cfg.N * cfg.c
+    counts = np.zeros(S, dtype=np.int64)
+    counts[[0, 5, 6, 17, 30, 47]] = [700, 1, 300, 513, 630, 256]
+    assert counts.sum() == cfg.T * cfg.k
+    offsets = np.zeros(S + 1, dtype=np.int32)
+    offsets[1:] = np.cumsum(counts)
+    rng = np.random.default_rng(5)
+    slot_expert = rng.integers(0, cfg.E, size=S).astype(np.int32)
+    w = expert_weights(cfg, threads=4)
+    xph = f32_to_bf16_bits(rng.standard_normal((cfg.T * cfg.k, cfg.d)).astype(np.float32))
+    shape = lz.Shape.from_config(cfg)
+    w1, w2 = to_dev(w["w1"][slot_expert], True), to_dev(w["w2"][slot_expert], True)
+    xp, off = to_dev(xph, True), to_dev(offsets)
+    nbytes = lz.lz_ffn_workspace_bytes(shape)
+    ws = torch.empty(nbytes, dtype=torch.uint8, device=DEV)
+    lz.lz_ffn_tiles(off, shape, ws, nbytes)
+    outs = []
+    for _ in range(3):
+        yp = torch.zeros((cfg.T * cfg.k, cfg.d), dtype=torch.bfloat16, device=DEV)
+        lz.lz_ffn_up(xp, w1, shape, ws, nbytes)
+        lz.lz_ffn_down(w2, shape, yp, ws, nbytes)
+        torch.cuda.synchronize()
+        outs.append(yp)
+    assert torch.equal(outs[0].view(torch.int16), outs[1].view(torch.int16))
+    assert torch.equal(outs[0].view(torch.int16), outs[2].view(torch.int16))
+    ref = om.expert_ffn_rows(xph, offsets, slot_expert, w["w1"], w["w2"], cfg.act)
+    assert rel_err(to_host(outs[2]), ref) <= 2e-2
+
+
 def test_expert_ffn_clips_bad_offsets():
     cfg = scaled(CONFIGS["c1_tiny"], dtype="bf16", act="swiglu", T=256, k=2, d=256, ffn=128, N=2, c=2)
     shape = lz.Shape.from_config(cfg)
