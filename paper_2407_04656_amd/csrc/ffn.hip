@@ -434,6 +434,25 @@ __device__ __forceinline__ void gemm_tile(const MfmaArgs& a, char* smem, int slo
 #pragma unroll
     for (int i = 1; i < 4; ++i) wf[set][i] = *(const bf16x8*)(stage + wbase + i * 32 * kRowBytes + fragoff[ks]);
   };
+  auto read_one = [&](const char* stage, int ks, int set, int r) {  // r-th fragment in that order
+    if (r == 0) wf[set][0] = *(const bf16x8*)(stage + wbase + fragoff[ks]);
+    else if (r <= XF) xf[set][r - 1] = *(const bf16x8*)(stage + xbase + (r - 1) * 32 * kRowBytes + fragoff[ks]);
+    else wf[set][r - XF] = *(const bf16x8*)(stage + wbase + (r - XF) * 32 * kRowBytes + fragoff[ks]);
+  };
+  // Fragment reads and direct-to-LDS loads of one slice, alternating in program order.  The
+  // compiler cannot tell that a load's LDS destination and a fragment read never overlap, so it
+  // keeps the two kinds in the order written: written as "all loads, then all reads", the reads
+  // would reach the LDS queue only after the last load and the next slice's first MFMAs would
+  // each wait out an LDS round trip.
+  auto reads_and_loads = [&](const char* rd_stage, int ks, int set, int ld_stage, int step, int q0, int q1) {
+    constexpr int NR = 4 + XF;
+    const int NL = q1 - q0;
+#pragma unroll
+    for (int r = 0; r < NR; ++r) {
+      read_one(rd_stage, ks, set, r);
+      issue(ld_stage, step, q0 + (NL * r) / NR, q0 + (NL * (r + 1)) / NR);
+    }
+  };
   auto mma = [&](int set) {
 #pragma unroll
     for (int i = 0; i < 4; ++i)
@@ -453,8 +472,7 @@ __device__ __forceinline__ void gemm_tile(const MfmaArgs& a, char* smem, int slo
     const int cur = kt & 1;
     const char* st = smem + cur * kStageBytes;
     const char* nx = smem + (cur ^ 1) * kStageBytes;
-    issue(cur ^ 1, kt + 1, kAfterBarrier, kLoads);
-    read_frags(st, 1, 1);
+    reads_and_loads(st, 1, 1, cur ^ 1, kt + 1, kAfterBarrier, kLoads);
     mma(0);
     sched_slice<0, 4 + XF, 4 * XF, kSlice0>();
     read_frags(st, 2, 0);
@@ -465,8 +483,7 @@ __device__ __forceinline__ void gemm_tile(const MfmaArgs& a, char* smem, int slo
     sched_slice<0, 4 + XF, 4 * XF, 0>();
     __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wave's loads of the next stage are in LDS
     __syncthreads();                     // everyone's are; nobody reads stage `cur` any more
-    issue(cur, kt + 2, 0, kAfterBarrier);
-    read_frags(nx, 0, 0);
+    reads_and_loads(nx, 0, 0, cur, kt + 2, 0, kAfterBarrier);
     mma(1);
     sched_slice<0, 4 + XF, 4 * XF, kAfterBarrier>();
   }
