@@ -10,6 +10,8 @@ never route through it.
 Modules
   moe_layer  routing (Sec. 2.1), the token dispatcher (Algorithm 1, Sec. 4.2), the
              per-slot row maps, permute, the expert FFN and the gate-weighted combine
+  moe_backward  the layer's backward pass by the chain rule (gradients of inputs, gates,
+             logits and expert weights, replica sums as in Sec. 5)
   planner    replica allocation (Eq. 1), MRO / spread placement (Sec. 4.1, Theorem 1),
              recovery probability by enumeration (Sec. 6.3) and re-planning after
              rank loss (Sec. 4.3)
