@@ -174,6 +174,75 @@ int32_t lz_unpermute_combine(const void* yp, const int32_t* pair_to_row,
                              const float* topk_gates, const lz_shape* shape,
                              void* y, void* stream);
 
+/* ---------------------------------------------------------------- training: forward that keeps
+ * its intermediates, and the backward pass.
+ *
+ * The paper trains the layer (Sec. 5: expert gradients are all-reduced over each expert's
+ * replicas) without printing backward formulas; what these calls compute is the chain rule on
+ * the forward of Sec. 2.1, one step per call, in reverse order:
+ *
+ *   lz_combine_backward   dgates[t,kk] = <dy[t], yp[row]>,  dyp[row] = gates[t,kk] dy[t]
+ *   lz_ffn_backward       dH = dyp W2,  dW2[s] = dyp_s^T H_s,  dZ = dH * act'(Z),
+ *                         dxp = dZ W1,  dW1[s] = dZ_s^T xp_s            (per slot s)
+ *   lz_permute_backward   dx[t] = sum_kk dxp[row(t,kk)]
+ *   lz_route_backward     dlogits[t, ids[t,j]] = g_j (dg_j - sum_i g_i dg_i), 0 elsewhere
+ *   lz_reduce_replica_grads   dW[e] = sum of dW[s] over the slots s holding expert e
+ *
+ * bf16 tensors only (LZ_ESHAPE otherwise), products accumulated in fp32, every stored tensor
+ * rounded to bf16 once.  The FFN calls need d % 256 == 0, ffn % 64 == 0, d*ffn*4 < 2^31,
+ * T*k <= 2^22 and N*c*max(d, 2*ffn) < 2^31.  All tensor pointers are device memory, 16-byte
+ * aligned; `ws` is 256-byte aligned device memory of lz_train_workspace_bytes(shape) bytes that
+ * serves one call at a time. */
+size_t lz_train_workspace_bytes(const lz_shape* shape);
+
+/* wt[s] = w[s]^T for s < S: w dev [S, rows, cols] -> wt dev [S, cols, rows], bf16, rows and
+ * cols multiples of 64.  lz_ffn_backward contracts over the rows of a weight matrix, and the
+ * MFMA kernel wants its operands contiguous along the contraction: the caller keeps these
+ * transposes beside the weights and refreshes them when the weights change. */
+int32_t lz_transpose_weights(const void* w, int32_t S, int32_t rows, int32_t cols, void* wt, void* stream);
+
+/* lz_expert_ffn that also returns what the backward needs: z = xp W1^T (pre-activation,
+ * [P, n1]; SwiGLU: columns [0,ffn) gate, [ffn,2ffn) up) and h = act(z) [P, ffn].  The
+ * activation is applied to the bf16-rounded z.  Rows outside every slot are left untouched.
+ *   xp dev [P,d], w1 dev [S,n1,d], w2 dev [S,d,ffn], z dev [P,n1] out, h dev [P,ffn] out, yp dev [P,d] out */
+int32_t lz_ffn_forward_train(const void* xp, const int32_t* slot_offsets, const void* w1, const void* w2,
+                             const lz_shape* shape, void* z, void* h, void* yp, void* ws, size_t ws_bytes,
+                             void* stream);
+
+/* Backward of lz_unpermute_combine.  A dyp row that no pair maps to is left untouched.
+ *   dy dev [T,d], yp dev [P,d], dyp dev [P,d] out, dgates dev [T,k] f32 out */
+int32_t lz_combine_backward(const void* dy, const void* yp, const int32_t* pair_to_row,
+                            const float* topk_gates, const lz_shape* shape, void* dyp, float* dgates,
+                            void* stream);
+
+/* Backward of the expert FFN over the permuted buffer.
+ *   dyp, xp dev [P,d]; z dev [P,n1], h dev [P,ffn] from lz_ffn_forward_train
+ *   w1t dev [S,d,n1] = transposes of w1, w2t dev [S,ffn,d] = transposes of w2
+ *   dxp dev [P,d] out (rows outside every slot untouched)
+ *   dw1 dev [S,n1,d] out, dw2 dev [S,d,ffn] out: each slot's own gradient, zero for an empty slot */
+int32_t lz_ffn_backward(const void* dyp, const void* xp, const void* z, const void* h,
+                        const int32_t* slot_offsets, const void* w1t, const void* w2t,
+                        const lz_shape* shape, void* dxp, void* dw1, void* dw2, void* ws,
+                        size_t ws_bytes, void* stream);
+
+/* Backward of the reshuffle: dx[t,:] = sum_{kk<k} dxp[pair_to_row[t*k+kk], :], fp32 sum in
+ * ascending kk, rounded once.  Same dtypes as lz_unpermute_combine.  dxp dev [P,d], dx dev [T,d] out. */
+int32_t lz_permute_backward(const void* dxp, const int32_t* pair_to_row, const lz_shape* shape,
+                            void* dx, void* stream);
+
+/* Backward of the top-k softmax gates of lz_route (the selection is piecewise constant).
+ *   dgates, topk_gates dev [T,k] f32; topk_ids dev [T,k] i32; dlogits dev [T,E] f32 out */
+int32_t lz_route_backward(const float* dgates, const float* topk_gates, const int32_t* topk_ids,
+                          const lz_shape* shape, float* dlogits, void* stream);
+
+/* The sum an all-reduce over an expert's replica set leaves on every replica (Sec. 5), for
+ * replicas that live on one device: dw[e] = sum over slots s with slot_expert[s] == e of
+ * dw_slot[s], ascending s, fp32 sum, one rounding; an expert without a slot gets zero.
+ *   dw_slot dev [S, elems_per_slot] bf16, slot_expert dev [S] i32, dw dev [E, elems_per_slot] bf16 out;
+ *   elems_per_slot % 8 == 0 */
+int32_t lz_reduce_replica_grads(const void* dw_slot, const int32_t* slot_expert, int32_t S, int32_t E,
+                                int64_t elems_per_slot, void* dw, void* stream);
+
 /* ---------------------------------------------------------------- host planning */
 
 /* Replica allocation, Eq. 1 (Sec. 4.1): experts in ascending load t_e (ties: lower id)

@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "liblazarus_moe.so")
-SOURCES = ["route.hip", "plan.hip", "permute_combine.hip", "ffn.hip", "misc.hip", "planner.cpp"]
+SOURCES = ["route.hip", "plan.hip", "permute_combine.hip", "ffn.hip", "backward.hip", "misc.hip", "planner.cpp"]
 
 FLAGS = [
     "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared",

@@ -1,0 +1,565 @@
+// Grouped bf16 GEMM on the gfx950 matrix cores and the row-tile table it draws its work from;
+// shared by the forward and the backward translation units (device code, not part of the C ABI).
+//
+//   C[rows of a slot, n] = epi( sum_k A[row, k] * W[slot][n, k] )      both operands K-contiguous
+//
+// bf16 path (gfx950 MFMA): persistent kernel, one workgroup per CU, drawing 256x256 tiles from
+// its XCD's queue.  4 waves in 2x2, each wave a 128x128 patch = 4x4
+// v_mfma_f32_32x32x16_bf16 accumulators (fp32, 256 AGPRs).  Both operands are K-contiguous
+// and are streamed HBM -> LDS with 16-byte buffer loads that write LDS directly, through two
+// LDS stages of 64 K-columns; fragment reads are software pipelined over two register sets.
+// The XOR swizzle that keeps the ds_read_b128 fragment reads conflict-free is applied on the
+// global-address side because a direct-to-LDS load fixes the LDS side to lane order.  Buffer
+// descriptors bound every load, so ragged tiles cannot fault.  The MFMA takes the weight
+// fragment as its row operand, which leaves each lane with 4 consecutive output columns per
+// accumulator group: 8-byte bf16 stores, no LDS transpose.  For SwiGLU the weight tile
+// interleaves 32-row fragments of Wg and Wu, so the gate and up values of one output element
+// sit in the same lane and register index.
+#pragma once
+#include "lz_common.h"
+
+namespace {
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
+
+constexpr int kTileHeader = 64;  // ints before the tile arrays; [0] = number of row tiles
+constexpr int kGroupM = 4;       // row tiles of a work unit (same slot)
+constexpr int kGroupN = 8;       // column tiles of a work unit
+
+enum { EPI_NONE = 0, EPI_GELU = 1, EPI_SWIGLU = 2 };
+
+struct TileTable {
+  int32_t* header;
+  int32_t* slot;
+  int32_t* row0;
+  int32_t* row_end;
+  int32_t* units[2];  // per GEMM (0 = up, 1 = down): 8 lists of unit_cap[g] work units, one list per XCD
+  int unit_cap[2];
+  int capacity;
+};
+
+constexpr int kUnitCount = 16;  // header[kUnitCount + 16*g + x] = length of XCD x's unit list for GEMM g
+
+// Row tiles are listed slot after slot; with group > 1 every slot's list is padded (slot = -1)
+// to a multiple of `group`, so that a group of consecutive row tiles never spans two slots.
+inline int tile_capacity(long long P, int S, int BM, int group) {
+  const long long n = (P + BM - 1) / BM + (long long)S * group;
+  return int((n + group - 1) / group * group);
+}
+
+// Room in one XCD's list of work units (a unit = one row group x kGroupN column tiles): twice
+// an eighth of the worst-case number of units, so that lists of equal cost but unequal length
+// normally fit as they are.
+inline int unit_capacity(int capacity, int group, int n_tiles) {
+  if (n_tiles <= 0) return 0;
+  const long long units = (long long)(capacity / group) * ((n_tiles + kGroupN - 1) / kGroupN);
+  return int((units + 7) / 8 * 2);
+}
+
+inline size_t tile_table_bytes(long long P, int S, int BM, int group, int n_up, int n_down) {
+  const int cap = tile_capacity(P, S, BM, group);
+  const size_t ints = kTileHeader + 3 * (size_t)cap +
+                      8 * ((size_t)unit_capacity(cap, group, n_up) + unit_capacity(cap, group, n_down));
+  return lz::align256(sizeof(int32_t) * ints);
+}
+
+inline TileTable carve_tiles(void* base, long long P, int S, int BM, int group, int n_up, int n_down) {
+  TileTable t;
+  t.capacity = tile_capacity(P, S, BM, group);
+  t.header = (int32_t*)base;
+  t.slot = t.header + kTileHeader;
+  t.row0 = t.slot + t.capacity;
+  t.row_end = t.row0 + t.capacity;
+  t.unit_cap[0] = unit_capacity(t.capacity, group, n_up);
+  t.unit_cap[1] = unit_capacity(t.capacity, group, n_down);
+  t.units[0] = t.row_end + t.capacity;
+  t.units[1] = t.units[0] + 8 * (size_t)t.unit_cap[0];
+  return t;
+}
+
+__device__ __forceinline__ void clip_slot(const int32_t* slot_offsets, int s, long long P, long long* a,
+                                          long long* b) {
+  long long lo = slot_offsets[s], hi = slot_offsets[s + 1];
+  lo = lo < 0 ? 0 : (lo > P ? P : lo);
+  hi = hi < lo ? lo : (hi > P ? P : hi);
+  *a = lo;
+  *b = hi;
+}
+
+// slot_offsets -> row tiles.  Offsets are clipped to [0, P] and made non-decreasing.
+//
+// For the MFMA GEMMs (n_tiles_up/down > 0) the kernel also deals each GEMM's work units (one
+// row group x kGroupN column tiles) to the 8 XCDs' queues: in (row group, column group) order,
+// eight at a time, alternate eights in opposite directions.  The XCDs thus work on neighbouring
+// column groups of the same row group at the same time and share its activation panel in the
+// memory-side cache, and a regular pattern of large and small units (a narrow last column
+// group, say) does not pile the large ones on the same XCDs; what imbalance is left the GEMM
+// kernel evens out by itself.  (Dealing by estimated cost, least-loaded queue first, was
+// within 2 % of this and costs a serial pass over the units; dealing the full row groups
+// first and the ragged ones last measured 1-5 % slower.)
+__global__ __launch_bounds__(256) void build_tiles_kernel(const int32_t* __restrict__ slot_offsets,
+                                                          int S, long long P, int BM, int group,
+                                                          int n_tiles_up, int n_tiles_down, TileTable t) {
+  __shared__ int s_first[lz::kMaxN * lz::kMaxC + 1];
+  // padded tile count of every slot (parallel: the offsets come from global memory), then one
+  // thread's running sum over LDS
+  for (int s = threadIdx.x; s < S; s += blockDim.x) {
+    long long a, b;
+    clip_slot(slot_offsets, s, P, &a, &b);
+    const int tiles = int((b - a + BM - 1) / BM);
+    s_first[s + 1] = (tiles + group - 1) / group * group;
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    int running = 0;
+    for (int s = 0; s < S; ++s) {
+      int padded = s_first[s + 1];
+      if (running + padded > t.capacity) padded = t.capacity - running;  // cannot happen for clipped offsets
+      s_first[s] = running;
+      running += padded;
+    }
+    s_first[S] = running;
+    t.header[0] = running;
+    for (int i = 40; i < 64; ++i) t.header[i] = 0;  // tile-queue tickets of the GEMM kernels
+  }
+  __syncthreads();
+  for (int s = threadIdx.x; s < S; s += blockDim.x) {
+    long long a, b;
+    clip_slot(slot_offsets, s, P, &a, &b);
+    for (int i = s_first[s]; i < s_first[s + 1]; ++i) {
+      const long long r0 = a + (long long)(i - s_first[s]) * BM;
+      t.slot[i] = r0 < b ? s : -1;  // -1: padding entry, no rows
+      t.row0[i] = int(r0 < b ? r0 : b);
+      t.row_end[i] = int(b);
+    }
+  }
+  // deal the units, in (row group, column group) order, to the XCD queues in rows of eight,
+  // alternate rows in opposite directions
+  const int n_groups = s_first[S] / group;
+  for (int which = 0; which < 2; ++which) {
+    const int nt = which == 0 ? n_tiles_up : n_tiles_down;
+    const int ncg = (nt + kGroupN - 1) / kGroupN;
+    const int n_units = n_groups * ncg;  // 0 on the generic path
+    const int cap = t.unit_cap[which];
+    for (int u = threadIdx.x; u < n_units; u += blockDim.x) {
+      const int row = u / 8, i = u % 8;
+      const int x = (row & 1) ? 7 - i : i;
+      if (row < cap) t.units[which][(size_t)x * cap + row] = u;  // n_units <= 4 * cap: always true
+    }
+    if (threadIdx.x < 8) {
+      const int rows = n_units / 8, rest = n_units % 8;
+      const int i = (rows & 1) ? 7 - (int)threadIdx.x : (int)threadIdx.x;  // position of this XCD in the last row
+      t.header[kUnitCount + 16 * which + threadIdx.x] = rows + (i < rest ? 1 : 0);
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// gfx950 MFMA kernel, bf16 in / fp32 accumulate / bf16 out
+// ------------------------------------------------------------------------------------------
+constexpr int BM = 256, BN = 256, BK = 64;
+constexpr int kRowBytes = BK * 2;                  // one tile row of a stage in LDS: 128 B = 8 chunks of 16 B
+constexpr int kStageBytes = (BM + BN) * kRowBytes; // activation tile (up to 256 rows), then weight tile
+constexpr int kLdsBytes = 2 * kStageBytes;         // two stages: 128 KiB of the CU's 160 KiB
+
+struct MfmaArgs {
+  const uint16_t* A;    // [P, K]
+  const uint16_t* W;    // [S, w_rows, K]
+  uint16_t* C;          // [P, n_out]
+  long long P;
+  int K;
+  int w_rows;           // weight rows per slot
+  int n_out;            // output columns
+  int up_row0;          // SwiGLU: first row of the up projection inside a slot's W
+  int n_tiles;          // column tiles per row tile
+  int which;            // 0 = GEMM-1, 1 = GEMM-2: which unit lists and tickets of the tile table
+  TileTable t;
+  // Ragged-K mode (VARK, the weight-gradient contractions): every slot owns rows_per_slot rows
+  // of C (row index = slot * rows_per_slot + m) and its own contraction length.  Slot s's
+  // operands are the blocks A_s [rows_per_slot, K_s] at A + rows_per_slot * kinfo[2s] and
+  // W_s [w_rows, K_s] at W + w_rows * kinfo[2s], with K_s = kinfo[2s+1] a multiple of 64.
+  const int32_t* kinfo;
+  int rows_per_slot;
+};
+
+// Activations on the fp32 accumulators of the bf16 path.  The result is rounded to bf16
+// (relative step 2^-9), so hardware exp2 / rcp (1 ulp) are used; erf is the
+// Abramowitz-Stegun 7.1.26 rational form, absolute error below 2e-7 before those.
+__device__ __forceinline__ float silu_fast(float v) {
+  return v * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.44269504088896341f * v));
+}
+__device__ __forceinline__ float gelu_fast(float v) {
+  const float x = fabsf(v) * 0.70710678118654752440f;
+  const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f, x, 1.0f));
+  float p = fmaf(1.061405429f, t, -1.453152027f);
+  p = fmaf(p, t, 1.421413741f);
+  p = fmaf(p, t, -0.284496736f);
+  p = fmaf(p, t, 0.254829592f);
+  const float e = __builtin_amdgcn_exp2f(-1.44269504088896341f * x * x);
+  const float erf_abs = 1.0f - p * t * e;         // erf(|v| / sqrt 2)
+  return 0.5f * v + 0.5f * fabsf(v) * erf_abs;    // 0.5 v (1 + sign(v) erf_abs)
+}
+
+// Two fp32 -> one dword of two bf16, round to nearest even (v_cvt_pk_bf16_f32 on gfx950).
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+  const f32x2 v = {lo, hi};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
+}
+
+// 16-byte chunk c of tile row r lives at chunk position c ^ swz(r) of its 128-byte LDS row.
+// LDS has 64 banks of 4 B, so a ds_read_b128 is served 16 lanes at a time: 16 consecutive
+// rows at one logical chunk must cover 16 distinct 16-byte bank groups (256 B = 2 rows), hence
+// the key row/2.
+__device__ __forceinline__ int swz(int row) { return (row >> 1) & 7; }
+
+// Scheduling hint for one 16-wide K slice of NM MFMAs: the ND ds_reads go out one per MFMA from
+// the start of the slice (the next slice waits on them), the NV direct-to-LDS loads are spread
+// evenly over the slice.
+template <int Q, int ND, int NM, int NV>
+__device__ __forceinline__ void sched_slice() {
+  if constexpr (Q < NM) {
+    constexpr int v = (NV * (Q + 1)) / NM - (NV * Q) / NM;
+    if constexpr (v > 0) __builtin_amdgcn_sched_group_barrier(0x020, v, 0);       // VMEM read
+    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                             // MFMA
+    if constexpr (Q < ND) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);      // DS read
+    sched_slice<Q + 1, ND, NM, NV>();
+  }
+}
+
+// One output tile of 64*XF rows x 256 weight rows.  XF = 32-row activation fragments per
+// wave: the 2x2 waves each own (32*XF) x 128 of the tile, so a slot's ragged last tile costs
+// MFMAs and activation loads only for its rows rounded up to 64.
+template <int EPI, int XF, bool VARK>
+__device__ __forceinline__ void gemm_tile(const MfmaArgs& a, char* smem, int slot, int row0, int row_end, int n0) {
+  constexpr int KS = BK / 16;             // 16-wide MFMA slices per stage
+  constexpr int kLoadsX = 2 * XF;         // 1-KiB wave loads per wave for the activation tile (8 rows each)
+  constexpr int kLoadsW = 8;              // ... for the 256-row weight tile
+  // The empty asm keeps the per-lane address arithmetic below inside the tile: hoisted out of
+  // the caller's tile loop it would be carried in registers through the whole kernel and spill.
+  int tid = threadIdx.x;
+  asm volatile("" : "+v"(tid));
+  const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave >> 1, wn = wave & 1;
+
+  // ---- buffer descriptors: out-of-range loads return zero instead of faulting.  The activation
+  // descriptor covers just this tile's rows, so 32-bit offsets do however large P is.
+  const int n_rows = row_end - row0 < BM ? row_end - row0 : BM;
+  int K = a.K;
+  const uint16_t* tileA;
+  const uint16_t* tileW;
+  uint32_t w_extent;  // bytes of the weight block the descriptor covers
+  if constexpr (VARK) {
+    // the weight descriptor starts at this tile's first weight row: 256 rows of K_s stay far
+    // below 2^31 bytes whatever the slot's length
+    const long long col0 = a.kinfo[2 * slot];
+    K = a.kinfo[2 * slot + 1];
+    tileA = a.A + (size_t)a.rows_per_slot * col0 + (size_t)(row0 - slot * a.rows_per_slot) * K;
+    tileW = a.W + (size_t)a.w_rows * col0 + (size_t)n0 * K;
+    const int w_left = a.w_rows - n0 < BN ? a.w_rows - n0 : BN;
+    w_extent = (uint32_t)w_left * (uint32_t)K * 2u;
+  } else {
+    tileA = a.A + (size_t)row0 * K;
+    tileW = a.W + (size_t)slot * a.w_rows * K;
+    w_extent = (uint32_t)((unsigned long long)a.w_rows * K * 2);
+  }
+  const __amdgpu_buffer_rsrc_t rsrcA = __builtin_amdgcn_make_buffer_rsrc(
+      (void*)tileA, 0, (int)((uint32_t)n_rows * (uint32_t)K * 2u), 0x00020000);
+  const __amdgpu_buffer_rsrc_t rsrcB = __builtin_amdgcn_make_buffer_rsrc((void*)tileW, 0, (int)w_extent, 0x00020000);
+  const __amdgpu_buffer_rsrc_t rsrcNull = __builtin_amdgcn_make_buffer_rsrc((void*)a.A, 0, 0, 0x00020000);
+
+  // ---- per-lane global offsets of the direct-to-LDS loads of one stage.
+  // Load u of an operand tile fills LDS bytes [u*1024, u*1024+1024): 8 whole rows, lane l
+  // landing at row 8u + l/8, 16-byte chunk l%8.  That LDS chunk must hold logical chunk
+  // (l%8) ^ swz(row), so the lane fetches that one (the swizzle is applied on the global side
+  // because a direct-to-LDS load fixes the LDS side to lane order).
+  int voffX[kLoadsX], voffW[kLoadsW];
+#pragma unroll
+  for (int i = 0; i < kLoadsX; ++i) {
+    const int r = (wave * kLoadsX + i) * 8 + (lane >> 3);
+    const int chunk = (lane & 7) ^ swz(r);
+    const int ga = r < n_rows ? r : n_rows - 1;  // rows past the tile's end repeat its last row (never stored)
+    voffX[i] = (int)(((uint32_t)ga * (uint32_t)K + (uint32_t)chunk * 8u) * 2u);
+  }
+#pragma unroll
+  for (int i = 0; i < kLoadsW; ++i) {
+    const int r = (wave * kLoadsW + i) * 8 + (lane >> 3);
+    const int chunk = (lane & 7) ^ swz(r);
+    int gb;
+    if (EPI == EPI_SWIGLU) {
+      const int f = r >> 5;  // fragment index: even = gate rows, odd = up rows
+      gb = n0 + (f >> 1) * 32 + (r & 31) + ((f & 1) ? a.up_row0 : 0);
+    } else {
+      gb = VARK ? r : n0 + r;
+    }
+    voffW[i] = (int)(((uint32_t)gb * (uint32_t)K + (uint32_t)chunk * 8u) * 2u);
+  }
+
+  // ---- fragment read addresses: lane l reads row (l%32) of a 32-row fragment, logical chunk
+  // 2*ks + l/32 of the stage's K slice
+  int fragoff[KS];
+  {
+    const int r = lane & 31;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) fragoff[ks] = r * kRowBytes + (((ks * 2 + (lane >> 5)) ^ swz(r)) << 4);
+  }
+  const int xbase = wm * 32 * XF * kRowBytes;               // this wave's activation rows
+  const int wbase = BM * kRowBytes + wn * 128 * kRowBytes;  // this wave's 128 weight rows
+
+  f32x16 acc[4][XF];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < XF; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+  // ---- main loop: two LDS stages of 64 K-columns, and two register sets of fragments
+  // alternating over the four 16-wide slices so that the ds_reads of the next slice are in
+  // flight while the MFMAs of the current one run.  One barrier per step, placed after the
+  // reads of the step's last slice have been issued: past it nobody reads the current stage any
+  // more, so the loads of step kt+2 can start into it, and the next stage (whose loads every
+  // wave has waited for before the barrier) can be read.
+  //
+  // The loads of step kt+2 are not issued in one burst: a wave that issues a burst stands still
+  // until the texture unit has accepted it, and the MFMA pipe with it.  Six go out during the
+  // slice after barrier kt, the rest during slice 0 of step kt+1, none in slices 1 and 2, which
+  // leaves every load two slices to land before the wait at the end of step kt+1; the
+  // activation loads go first.  (Measured on three workloads: 6 + rest + 0 beats 8 + half + half
+  // by 2-11 %, and 4, 5, 7, 8, 10, 12 or all 16 after the barrier; activations first is 0.7 %
+  // ahead of weights first on the first GEMM and level on the second.)
+  const int k_steps = K / BK;
+  constexpr int kLoads = kLoadsW + kLoadsX;
+  auto issue = [&](int stage, int step, int q0, int q1) {
+    // a step past the end of K is "loaded" through a zero-length descriptor: no memory traffic
+    const bool real = step < k_steps;
+    const __amdgpu_buffer_rsrc_t ra = real ? rsrcA : rsrcNull;
+    const __amdgpu_buffer_rsrc_t rb = real ? rsrcB : rsrcNull;
+    char* sX = smem + stage * kStageBytes;
+    char* sW = sX + BM * kRowBytes;
+#pragma unroll
+    for (int q = q0; q < q1; ++q) {
+      if (q < kLoadsX) {
+        const int u = wave * kLoadsX + q;
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(ra, (__attribute__((address_space(3))) void*)(sX + u * 1024), 16,
+                                                 voffX[q], step * BK * 2, 0, 0);
+      } else {
+        const int u = wave * kLoadsW + (q - kLoadsX);
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rb, (__attribute__((address_space(3))) void*)(sW + u * 1024), 16,
+                                                 voffW[q - kLoadsX], step * BK * 2, 0, 0);
+      }
+    }
+  };
+  constexpr int kAfterBarrier = 6;                 // loads issued in the slice after the barrier,
+  constexpr int kSlice0 = kLoads - kAfterBarrier;  // and in slice 0 of the next step
+  bf16x8 xf[2][XF], wf[2][4];
+  // read order = order of first use by the MFMAs (weight fragment 0, all activation fragments,
+  // weight fragments 1..3)
+  auto read_frags = [&](const char* stage, int ks, int set) {
+    wf[set][0] = *(const bf16x8*)(stage + wbase + fragoff[ks]);
+#pragma unroll
+    for (int j = 0; j < XF; ++j) xf[set][j] = *(const bf16x8*)(stage + xbase + j * 32 * kRowBytes + fragoff[ks]);
+#pragma unroll
+    for (int i = 1; i < 4; ++i) wf[set][i] = *(const bf16x8*)(stage + wbase + i * 32 * kRowBytes + fragoff[ks]);
+  };
+  auto read_one = [&](const char* stage, int ks, int set, int r) {  // r-th fragment in that order
+    if (r == 0) wf[set][0] = *(const bf16x8*)(stage + wbase + fragoff[ks]);
+    else if (r <= XF) xf[set][r - 1] = *(const bf16x8*)(stage + xbase + (r - 1) * 32 * kRowBytes + fragoff[ks]);
+    else wf[set][r - XF] = *(const bf16x8*)(stage + wbase + (r - XF) * 32 * kRowBytes + fragoff[ks]);
+  };
+  // Fragment reads and direct-to-LDS loads of one slice, alternating in program order.  The
+  // compiler cannot tell that a load's LDS destination and a fragment read never overlap, so it
+  // keeps the two kinds in the order written: written as "all loads, then all reads", the reads
+  // would reach the LDS queue only after the last load and the next slice's first MFMAs would
+  // each wait out an LDS round trip.
+  auto reads_and_loads = [&](const char* rd_stage, int ks, int set, int ld_stage, int step, int q0, int q1) {
+    constexpr int NR = 4 + XF;
+    const int NL = q1 - q0;
+#pragma unroll
+    for (int r = 0; r < NR; ++r) {
+      read_one(rd_stage, ks, set, r);
+      issue(ld_stage, step, q0 + (NL * r) / NR, q0 + (NL * (r + 1)) / NR);
+    }
+  };
+  auto mma = [&](int set) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int j = 0; j < XF; ++j)
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[set][i], xf[set][j], acc[i][j], 0, 0, 0);
+  };
+
+  issue(0, 0, 0, kLoads);
+  issue(1, 1, 0, kAfterBarrier);
+  // s_waitcnt with only vmcnt set (bits [3:0] and [15:14]): stage 1's first loads may still be in flight
+  __builtin_amdgcn_s_waitcnt(0x0F70 | kAfterBarrier);
+  __syncthreads();
+  read_frags(smem, 0, 0);
+
+  for (int kt = 0; kt < k_steps; ++kt) {
+    const int cur = kt & 1;
+    const char* st = smem + cur * kStageBytes;
+    const char* nx = smem + (cur ^ 1) * kStageBytes;
+    reads_and_loads(st, 1, 1, cur ^ 1, kt + 1, kAfterBarrier, kLoads);
+    mma(0);
+    sched_slice<0, 4 + XF, 4 * XF, kSlice0>();
+    read_frags(st, 2, 0);
+    mma(1);
+    sched_slice<0, 4 + XF, 4 * XF, 0>();
+    read_frags(st, 3, 1);
+    mma(0);
+    sched_slice<0, 4 + XF, 4 * XF, 0>();
+    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wave's loads of the next stage are in LDS
+    __syncthreads();                     // everyone's are; nobody reads stage `cur` any more
+    reads_and_loads(nx, 0, 0, cur, kt + 2, 0, kAfterBarrier);
+    mma(1);
+    sched_slice<0, 4 + XF, 4 * XF, kAfterBarrier>();
+  }
+  __builtin_amdgcn_s_waitcnt(0x0F70);  // drain the (empty) trailing loads before LDS is reused
+
+  // ---- epilogue.  acc[i][j] is the 32x32 block (weight fragment i) x (activation fragment j);
+  // lane l holds activation row j*32 + l%32 and, for g = 0..3, the 4 consecutive weight rows
+  // i*32 + 8g + 4*(l/32) + 0..3  -> 4 consecutive output columns.  Stored straight from there,
+  // a wave store would touch 32 rows with 16 bytes each; such partial-line writes cost the
+  // second GEMM 10 % (timed with the stores removed).  So each 32-row fragment goes through a
+  // per-wave LDS patch (the stages are dead by now; LDS serves a wave's accesses in order) and
+  // leaves as 16 bytes per lane, whole 128-byte lines at a time.
+  constexpr int kWaveCols = EPI == EPI_SWIGLU ? 64 : 128;  // output columns of this wave
+  constexpr int kPitch = kWaveCols * 2 + 16;               // patch row in bytes: 16-byte aligned, rows 4 banks apart
+  constexpr int kLanesPerRow = kWaveCols / 8;              // 16-byte pieces of a patch row
+  constexpr int kRowsPerStore = 64 / kLanesPerRow;
+  char* const patch = smem + wave * (32 * kPitch);
+  const int half = lane >> 5;
+#pragma unroll
+  for (int j = 0; j < XF; ++j) {
+    char* const prow = patch + (lane & 31) * kPitch;
+    if (EPI == EPI_SWIGLU) {
+#pragma unroll
+      for (int q = 0; q < 2; ++q)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          float o[4];
+#pragma unroll
+          for (int r = 0; r < 4; ++r) o[r] = silu_fast(acc[2 * q][j][4 * g + r]) * acc[2 * q + 1][j][4 * g + r];
+          uint2 pk;
+          pk.x = pack_bf16x2(o[0], o[1]);
+          pk.y = pack_bf16x2(o[2], o[3]);
+          *(uint2*)(prow + (q * 32 + 8 * g + 4 * half) * 2) = pk;
+        }
+    } else {
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          float o[4];
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            o[r] = acc[i][j][4 * g + r];
+            if (EPI == EPI_GELU) o[r] = gelu_fast(o[r]);
+          }
+          uint2 pk;
+          pk.x = pack_bf16x2(o[0], o[1]);
+          pk.y = pack_bf16x2(o[2], o[3]);
+          *(uint2*)(prow + (i * 32 + 8 * g + 4 * half) * 2) = pk;
+        }
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");  // keep the patch writes before the reads below
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+    for (int t = 0; t < 32 / kRowsPerStore; ++t) {
+      const int r = t * kRowsPerStore + lane / kLanesPerRow, piece = lane % kLanesPerRow;
+      const uint4 v = *(const uint4*)(patch + r * kPitch + piece * 16);
+      const int row = row0 + wm * 32 * XF + j * 32 + r;
+      const int col = n0 + wn * kWaveCols + piece * 8;  // n_out is a multiple of 8
+      if (row < row_end && col < a.n_out) *(uint4*)(a.C + (size_t)row * a.n_out + col) = v;
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");  // ... and the reads before the next fragment's writes
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+  }
+}
+
+[[maybe_unused]] constexpr int kTicket = 40;  // header[kTicket + 8*g + x]: next entry of XCD x's tile queue for GEMM g
+[[maybe_unused]] constexpr int kDone = 56;    // header[kDone + g]: workgroups of GEMM g's launch that have finished
+
+// Persistent kernel: one workgroup per CU.  Every XCD has a queue of tiles (its unit list, 32
+// tile slots per unit: kGroupM row tiles of one slot x kGroupN column tiles); a workgroup takes
+// the next slot of its own XCD's queue with an atomic ticket, and once that queue is empty
+// helps with the other XCDs' queues.  The 32 tiles an XCD works on at a time therefore share
+// their activation and weight panels through that XCD's L2, and each XCD drains its queue at
+// its own pace.  (The hardware hands the workgroups of an ordinary launch to the XCDs strictly
+// in order of their index: there an XCD whose tiles take longer holds back the workgroups
+// queued behind it for every other XCD, which costs 10-40 % on ragged plans.)
+template <int EPI, bool VARK = false>
+__global__ __launch_bounds__(256, 1) void gemm_mfma_kernel(MfmaArgs a) {
+#if defined(__HIP_DEVICE_COMPILE__)  // the host pass only needs the launch stub, not the gfx950 builtins
+  extern __shared__ __attribute__((aligned(1024))) char smem[];
+  constexpr int BN_OUT = EPI == EPI_SWIGLU ? BN / 2 : BN;
+  constexpr int kUnitTiles = kGroupM * kGroupN;
+  const int xcd = blockIdx.x % 8;  // workgroups are dealt round-robin to the 8 XCDs
+  const int n_col_groups = (a.n_tiles + kGroupN - 1) / kGroupN;
+  int* const ticket = a.t.header + kTicket + 8 * a.which;
+  const int32_t* const count = a.t.header + kUnitCount + 16 * a.which;
+  for (int hop = 0; hop < 8; ++hop) {
+    const int q = (xcd + hop) % 8;
+    const int n_slots = count[q] * kUnitTiles;
+    const int32_t* const list = a.t.units[a.which] + (size_t)q * a.t.unit_cap[a.which];
+    for (;;) {
+      __syncthreads();  // the previous tile's fragment reads are done: LDS may be reused
+      if (threadIdx.x == 0) *(volatile int*)smem = atomicAdd(ticket + q, 1);
+      __syncthreads();
+      const int t = __builtin_amdgcn_readfirstlane(*(volatile int*)smem);
+      __syncthreads();
+      if (t >= n_slots) break;  // every workgroup draws one ticket past the end of every queue, no more
+      const int unit = list[t / kUnitTiles];
+      const int within = t % kUnitTiles;
+      const int nt = (unit % n_col_groups) * kGroupN + within / kGroupM;
+      if (nt >= a.n_tiles) continue;
+      const int row_tile = (unit / n_col_groups) * kGroupM + within % kGroupM;
+      const int slot = a.t.slot[row_tile];
+      if (slot < 0) continue;
+      const int row0 = a.t.row0[row_tile];
+      const int row_end = a.t.row_end[row_tile];
+      const int n0 = nt * BN_OUT;
+      const int rows = row_end - row0;  // > 0; more than 256 means a full tile
+      if (rows > 192) gemm_tile<EPI, 4, VARK>(a, smem, slot, row0, row_end, n0);
+      else if (rows > 128) gemm_tile<EPI, 3, VARK>(a, smem, slot, row0, row_end, n0);
+      else if (rows > 64) gemm_tile<EPI, 2, VARK>(a, smem, slot, row0, row_end, n0);
+      else gemm_tile<EPI, 1, VARK>(a, smem, slot, row0, row_end, n0);
+    }
+  }
+  // the last workgroup to finish leaves the tickets at zero for the next launch on this table
+  if (threadIdx.x == 0) {
+    int* const done = a.t.header + kDone + a.which;
+    if (atomicAdd(done, 1) == (int)gridDim.x - 1) {
+      for (int q = 0; q < 8; ++q) ticket[q] = 0;
+      *done = 0;
+    }
+  }
+#endif
+}
+
+template <int EPI, bool VARK = false>
+int32_t launch_mfma(const MfmaArgs& a, hipStream_t st) {
+  void (*kern)(MfmaArgs) = gemm_mfma_kernel<EPI, VARK>;
+  static bool configured = false;  // per-process attribute; idempotent, so a benign race at worst
+  static int n_workgroups = 0;
+  if (!configured) {
+    if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes) !=
+        hipSuccess)
+      return LZ_EHIP;
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
+      return LZ_EHIP;
+    n_workgroups = cus >= 8 ? cus / 8 * 8 : 8;  // one per CU (the LDS a workgroup takes allows no more)
+    configured = true;
+  }
+  hipLaunchKernelGGL(kern, dim3(n_workgroups), dim3(256), kLdsBytes, st, a);
+  return lz::launch_status();
+}
+
+}  // namespace

@@ -122,6 +122,7 @@ __device__ __forceinline__ void fma8(float* acc, const u32x4& v, float g) {
 }
 
 // y[t, :] = sum_kk gate[t, kk] * yp[pair_to_row[t*k+kk], :]   bf16, 8 elements per lane-vector
+// (gates == nullptr: all gates 1, the backward of the reshuffle)
 __global__ __launch_bounds__(256) void combine_bf16_kernel(const u32x4* __restrict__ yp,
                                                            const int32_t* __restrict__ pair_to_row,
                                                            const float* __restrict__ gates, int T,
@@ -139,7 +140,7 @@ __global__ __launch_bounds__(256) void combine_bf16_kernel(const u32x4* __restri
     if (kk < k) {
       const int r = pair_to_row[t * k + kk];
       rows[kk] = (r >= 0 && r < P) ? r : -1;
-      g[kk] = gates[t * k + kk];
+      g[kk] = gates ? gates[t * k + kk] : 1.f;
     }
   }
   for (int v = lane; v < vec_per_row; v += lz::kWave) {
@@ -178,7 +179,7 @@ __global__ __launch_bounds__(256) void combine_elem_kernel(const void* __restric
       float val;
       if (BF16) val = lz::bf16_to_f32(((const uint16_t*)yp_)[(size_t)r * d + v]);
       else val = ((const float*)yp_)[(size_t)r * d + v];
-      acc = fmaf(gates[t * k + kk], val, acc);
+      acc = fmaf(gates ? gates[t * k + kk] : 1.f, val, acc);
     }
     if (BF16) ((uint16_t*)y_)[(size_t)t * d + v] = lz::f32_to_bf16(acc);
     else ((float*)y_)[(size_t)t * d + v] = acc;
@@ -233,12 +234,10 @@ extern "C" int32_t lz_permute_scatter(const void* x, const int32_t* pair_to_row,
   return lz::launch_status();
 }
 
-extern "C" int32_t lz_unpermute_combine(const void* yp, const int32_t* pair_to_row,
-                                        const float* topk_gates, const lz_shape* shape, void* y,
-                                        void* stream) {
-  if (!lz::shape_ok(shape)) return LZ_ESHAPE;
-  if (shape->T == 0) return LZ_OK;
-  if (!yp || !pair_to_row || !topk_gates || !y) return LZ_EINVAL;
+namespace {
+
+int32_t combine(const void* yp, const int32_t* pair_to_row, const float* topk_gates, const lz_shape* shape,
+                void* y, void* stream) {
   hipStream_t st = (hipStream_t)stream;
   const long long P = (long long)shape->T * shape->k;
   const unsigned blocks = unsigned((shape->T + kRowsPerBlock - 1) / kRowsPerBlock);
@@ -253,4 +252,23 @@ extern "C" int32_t lz_unpermute_combine(const void* yp, const int32_t* pair_to_r
                        topk_gates, shape->T, shape->k, P, shape->d, y);
   }
   return lz::launch_status();
+}
+
+}  // namespace
+
+extern "C" int32_t lz_unpermute_combine(const void* yp, const int32_t* pair_to_row,
+                                        const float* topk_gates, const lz_shape* shape, void* y,
+                                        void* stream) {
+  if (!lz::shape_ok(shape)) return LZ_ESHAPE;
+  if (shape->T == 0) return LZ_OK;
+  if (!yp || !pair_to_row || !topk_gates || !y) return LZ_EINVAL;
+  return combine(yp, pair_to_row, topk_gates, shape, y, stream);
+}
+
+extern "C" int32_t lz_permute_backward(const void* dxp, const int32_t* pair_to_row, const lz_shape* shape,
+                                       void* dx, void* stream) {
+  if (!lz::shape_ok(shape)) return LZ_ESHAPE;
+  if (shape->T == 0) return LZ_OK;
+  if (!dxp || !pair_to_row || !dx) return LZ_EINVAL;
+  return combine(dxp, pair_to_row, nullptr, shape, dx, stream);
 }

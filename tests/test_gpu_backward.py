@@ -1,0 +1,189 @@
+"""GPU parity of the training entry points (forward that keeps its intermediates, backward
+chain) against the fp64 backward oracle, through the C ABI."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2407_04656_amd as lz
+from oracle import moe_backward as ob
+from oracle import moe_layer as om
+from workloads import CONFIGS, expert_weights, f32_to_bf16_bits, step_inputs
+from workloads.configs import scaled
+
+from gpu_util import DEV, oracle_plan, rel_err, to_dev, to_host
+
+pytestmark = pytest.mark.gpu
+
+TOL = 2e-2   # bf16 tensors, fp32 accumulation: max |err| / max |ref|
+
+
+def _bf16(rng, shape, scale=1.0):
+    return f32_to_bf16_bits((rng.standard_normal(shape) * scale).astype(np.float32))
+
+
+def _ffn_backward_case(cfg, counts, seed):
+    S, P = cfg.N * cfg.c, cfg.T * cfg.k
+    assert len(counts) == S and sum(counts) == P
+    offsets = np.zeros(S + 1, dtype=np.int32)
+    offsets[1:] = np.cumsum(counts)
+    rng = np.random.default_rng(seed)
+    slot_expert = rng.integers(0, cfg.E, size=S).astype(np.int32)
+    w = expert_weights(cfg, threads=4)
+    n1 = w["w1"].shape[1]
+    xph = _bf16(rng, (P, cfg.d))
+    dyph = _bf16(rng, (P, cfg.d), 0.5)
+    shape = lz.Shape.from_config(cfg)
+    bf = torch.bfloat16
+    w1, w2 = to_dev(w["w1"][slot_expert], True), to_dev(w["w2"][slot_expert], True)
+    w1t = torch.empty((S, cfg.d, n1), dtype=bf, device=DEV)
+    w2t = torch.empty((S, cfg.ffn, cfg.d), dtype=bf, device=DEV)
+    lz.lz_transpose_weights(w1, S, n1, cfg.d, w1t)
+    lz.lz_transpose_weights(w2, S, cfg.d, cfg.ffn, w2t)
+    assert torch.equal(w1t.view(torch.int16), w1.transpose(1, 2).contiguous().view(torch.int16))
+    assert torch.equal(w2t.view(torch.int16), w2.transpose(1, 2).contiguous().view(torch.int16))
+    nbytes = lz.lz_train_workspace_bytes(shape)
+    assert nbytes > 0
+    ws = torch.empty(nbytes, dtype=torch.uint8, device=DEV)
+    xp, dyp, off = to_dev(xph, True), to_dev(dyph, True), to_dev(offsets)
+    z = torch.zeros((P, n1), dtype=bf, device=DEV)
+    h = torch.zeros((P, cfg.ffn), dtype=bf, device=DEV)
+    yp = torch.zeros((P, cfg.d), dtype=bf, device=DEV)
+    lz.lz_ffn_forward_train(xp, off, w1, w2, shape, z, h, yp, ws, nbytes)
+    dxp = torch.zeros((P, cfg.d), dtype=bf, device=DEV)
+    dw1 = torch.full((S, n1, cfg.d), 7.0, dtype=bf, device=DEV)
+    dw2 = torch.full((S, cfg.d, cfg.ffn), 7.0, dtype=bf, device=DEV)
+    lz.lz_ffn_backward(dyp, xp, z, h, off, w1t, w2t, shape, dxp, dw1, dw2, ws, nbytes)
+    torch.cuda.synchronize()
+
+    # forward intermediates
+    Xp = om.widen(xph)
+    Zref = np.zeros((P, n1))
+    for s in range(S):
+        a, b = offsets[s], offsets[s + 1]
+        Zref[a:b] = Xp[a:b] @ om.widen(w["w1"][slot_expert[s]]).T
+    assert rel_err(to_host(z), Zref) <= TOL
+    assert rel_err(to_host(h), ob.act_forward(Zref, cfg.act)) <= TOL
+    assert rel_err(to_host(yp), om.expert_ffn_rows(xph, offsets, slot_expert, w["w1"], w["w2"], cfg.act)) <= TOL
+    # backward
+    dxp_ref, dw1_ref, dw2_ref = ob.ffn_backward_rows(dyph, xph, offsets, slot_expert, w["w1"], w["w2"], cfg.act)
+    assert rel_err(to_host(dxp), dxp_ref) <= TOL
+    assert rel_err(to_host(dw1), dw1_ref) <= TOL
+    assert rel_err(to_host(dw2), dw2_ref) <= TOL
+    # slot by slot as well: a small slot's gradient must not hide behind a large one's scale
+    g1, g2 = om.widen(to_host(dw1)), om.widen(to_host(dw2))
+    for s in range(S):
+        if counts[s] == 0:
+            assert not g1[s].any() and not g2[s].any()
+        else:
+            assert np.max(np.abs(g1[s] - dw1_ref[s])) <= TOL * np.max(np.abs(dw1_ref[s]))
+            assert np.max(np.abs(g2[s] - dw2_ref[s])) <= TOL * np.max(np.abs(dw2_ref[s]))
+
+
+@pytest.mark.parametrize("act,d,ffn", [("gelu", 256, 256), ("swiglu", 256, 192), ("gelu", 512, 320),
+                                       ("swiglu", 512, 384)])
+def test_ffn_forward_train_and_backward_ragged(act, d, ffn):
+    cfg = scaled(CONFIGS["c1_tiny"], act=act, dtype="bf16", T=700, k=2, d=d, ffn=ffn, N=4, c=2)
+    # several row tiles, a tile boundary + 1, an empty slot, one-row slots, ragged tails; K of the
+    # weight gradients: 320, 128 (empty), 128 (one row), 512, 320, 256, 128, 128
+    _ffn_backward_case(cfg, [257, 0, 1, 512, 300, 255, 74, 1], 3)
+
+
+def test_ffn_backward_many_slots_mostly_empty():
+    cfg = scaled(CONFIGS["c1_tiny"], act="swiglu", dtype="bf16", T=600, k=2, d=256, ffn=128, N=4, c=5)
+    counts = [0] * 20
+    counts[3], counts[4], counts[11], counts[19] = 700, 64, 435, 1
+    _ffn_backward_case(cfg, counts, 9)
+
+
+def test_streaming_backward_kernels():
+    cfg = scaled(CONFIGS["c4_finegrained"], T=777, d=264, ffn=128, E=16, k=3, N=4, c=6)
+    inp = step_inputs(cfg)
+    ids, gates = om.route(inp["logits"], cfg.k)
+    plan = oracle_plan(cfg, ids)
+    disp = om.plan_dispatch(ids, inp["rank_tok_off"], plan, cfg.E, cfg.N, cfg.c)
+    rng = np.random.default_rng(4)
+    P = cfg.T * cfg.k
+    shape = lz.Shape.from_config(cfg)
+    dy, ypb = _bf16(rng, (cfg.T, cfg.d)), _bf16(rng, (P, cfg.d))
+    p2r = to_dev(disp["pair_to_row"])
+    g32 = to_dev(gates.astype(np.float32))
+    dyp = torch.zeros((P, cfg.d), dtype=torch.bfloat16, device=DEV)
+    dgates = torch.zeros((cfg.T, cfg.k), dtype=torch.float32, device=DEV)
+    lz.lz_combine_backward(to_dev(dy, True), to_dev(ypb, True), p2r, g32, shape, dyp, dgates)
+    dyp_ref, dg_ref = ob.combine_backward(dy, ypb, disp["pair_to_row"], gates.astype(np.float32))
+    got = om.widen(to_host(dyp))
+    assert np.all(np.abs(got - dyp_ref) <= 0.006 * np.abs(dyp_ref))         # one bf16 rounding (2^-8) and fp32 noise
+    assert np.allclose(to_host(dgates), dg_ref, rtol=1e-5, atol=1e-4)        # fp32 dot of d products
+    # dx = sum of the pair rows: the combine with unit gates, bit for bit
+    dx = torch.zeros((cfg.T, cfg.d), dtype=torch.bfloat16, device=DEV)
+    y1 = torch.zeros_like(dx)
+    lz.lz_permute_backward(dyp, p2r, shape, dx)
+    lz.lz_unpermute_combine(dyp, p2r, torch.ones_like(g32), shape, y1)
+    assert torch.equal(dx.view(torch.int16), y1.view(torch.int16))
+    dx_ref = ob.permute_backward(to_host(dyp), disp["pair_to_row"], cfg.k)
+    assert np.all(np.abs(om.widen(to_host(dx)) - dx_ref) <= 0.006 * np.abs(dx_ref) + 1e-6)
+    # gate backward
+    dlogits = torch.full((cfg.T, cfg.E), 3.0, dtype=torch.float32, device=DEV)
+    lz.lz_route_backward(dgates, g32, to_dev(ids), shape, dlogits)
+    dl_ref = ob.route_backward(to_host(dgates), gates.astype(np.float32), ids, cfg.E)
+    assert np.allclose(to_host(dlogits), dl_ref, rtol=1e-5, atol=1e-5 * np.max(np.abs(dl_ref)))
+    # replica sums
+    S, n = cfg.N * cfg.c, 1000 * 8
+    dws = _bf16(rng, (S, n))
+    dw = torch.full((cfg.E, n), 5.0, dtype=torch.bfloat16, device=DEV)
+    lz.lz_reduce_replica_grads(to_dev(dws, True), to_dev(plan), S, cfg.E, n, dw)
+    ref = ob.reduce_replica_grads(om.widen(dws), plan, cfg.E)
+    assert np.all(np.abs(om.widen(to_host(dw)) - ref) <= 0.006 * np.abs(ref) + 1e-6)
+
+
+@pytest.mark.parametrize("act", ["gelu", "swiglu"])
+def test_layer_backward_end_to_end(act):
+    cfg = scaled(CONFIGS["c4_finegrained"], act=act, T=900, d=256, ffn=128, E=16, k=3, N=4, c=6)
+    inp = step_inputs(cfg)
+    w = expert_weights(cfg, threads=4)
+    ids, gates = om.route(inp["logits"], cfg.k)
+    plan = oracle_plan(cfg, ids)
+    disp = om.plan_dispatch(ids, inp["rank_tok_off"], plan, cfg.E, cfg.N, cfg.c)
+    shape = lz.Shape.from_config(cfg)
+    layer = lz.MoELayer(shape, DEV)
+    layer.load_expert_weights(w["w1"], w["w2"], plan)
+    layer.set_plan(plan, inp["rank_tok_off"])
+    layer.enable_training()
+    rng = np.random.default_rng(12)
+    dy = _bf16(rng, (cfg.T, cfg.d))
+    y = layer.forward_train(to_dev(inp["logits"]), to_dev(inp["x"], True))
+    layer.backward(to_dev(dy, True))
+    torch.cuda.synchronize()
+    assert np.array_equal(to_host(layer.pair_to_row), disp["pair_to_row"])
+    assert rel_err(to_host(y), om.layer_output(inp["x"], ids, gates, w["w1"], w["w2"], act)) <= TOL
+    ref = ob.layer_backward(dy, inp["x"], ids, gates, disp["pair_to_row"], disp["row_to_pair"],
+                            disp["slot_offsets"], plan, w["w1"], w["w2"], act)
+    assert rel_err(to_host(layer.dx), ref["dx"]) <= TOL
+    assert rel_err(to_host(layer.dgates), ref["dgates"]) <= TOL
+    assert rel_err(to_host(layer.dw1), ref["dw1"]) <= TOL
+    assert rel_err(to_host(layer.dw2), ref["dw2"]) <= TOL
+    dl_ref = ob.route_backward(ref["dgates"], gates, ids, cfg.E)
+    assert rel_err(to_host(layer.dlogits), dl_ref) <= TOL
+    # a second pass on the same buffers gives the same bits (queues and scratch are reset)
+    first = [t.clone() for t in (layer.dx, layer.dw1, layer.dw2)]
+    layer.backward(to_dev(dy, True))
+    torch.cuda.synchronize()
+    for a, b in zip(first, (layer.dx, layer.dw1, layer.dw2)):
+        assert torch.equal(a.view(torch.int16), b.view(torch.int16))
+
+
+def test_training_entry_points_reject_what_they_do_not_serve():
+    f32 = lz.Shape.from_config(CONFIGS["c1_tiny"])
+    assert lz.lz_train_workspace_bytes(f32) == 0
+    odd = lz.Shape.from_config(scaled(CONFIGS["c1_tiny"], dtype="bf16", d=264, ffn=128))
+    assert lz.lz_train_workspace_bytes(odd) == 0
+    ok = lz.Shape.from_config(scaled(CONFIGS["c1_tiny"], dtype="bf16", d=256, ffn=128))
+    n = lz.lz_train_workspace_bytes(ok)
+    ws = torch.empty(n, dtype=torch.uint8, device=DEV)
+    dummy = torch.zeros(16, dtype=torch.uint8, device=DEV)
+    with pytest.raises(lz.LzError) as e:
+        lz.lz_ffn_backward(dummy, dummy, dummy, dummy, dummy, dummy, dummy, ok, dummy, dummy, dummy, ws, n - 256)
+    assert e.value.code == -3
+    with pytest.raises(lz.LzError) as e:
+        lz.lz_ffn_backward(dummy, dummy, dummy, dummy, dummy, dummy, dummy, f32, dummy, dummy, dummy, ws, n)
+    assert e.value.code == -2
