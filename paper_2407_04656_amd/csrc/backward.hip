@@ -196,12 +196,13 @@ __global__ __launch_bounds__(256) void act_backward_kernel(const u32x4* __restri
 
 // ---- ragged-K layout of the weight-gradient operands.
 // Slot s with R_s rows contracts over K_s = max(128, R_s rounded up to 64) columns, starting at
-// column col0_s = sum of the earlier K's: kinfo[2s] = col0_s, kinfo[2s+1] = K_s;
-// ktile_slot[i] = slot that the i-th 64-column tile belongs to; virt[s] = s (virtual row
-// offsets are virt * rows_per_slot, built by the caller's tile kernels from virt_d / virt_n1).
+// column col0_s = sum of the earlier K's: kinfo[2s] = col0_s, kinfo[2s+1] = K_s.  ktile[i]
+// describes the i-th 64-column tile of that layout for the transposing copy: {first source
+// row, end row of its slot, col0_s, K_s}, K_s = 0 for tiles past the last slot.  virt_w2 /
+// virt_w1 are the slot offsets of the S x rows_per_slot virtual rows of the two outputs.
 __global__ __launch_bounds__(256) void wgrad_plan_kernel(const int32_t* __restrict__ slot_offsets, int S, long long P,
-                                                         int rows_w2, int rows_w1, int32_t* __restrict__ kinfo,
-                                                         int32_t* __restrict__ ktile_slot,
+                                                         int rows_w2, int rows_w1, int n_ktiles,
+                                                         int32_t* __restrict__ kinfo, int4* __restrict__ ktile,
                                                          int32_t* __restrict__ virt_w2,
                                                          int32_t* __restrict__ virt_w1) {
   __shared__ int s_k[lz::kMaxN * lz::kMaxC + 1];
@@ -227,99 +228,75 @@ __global__ __launch_bounds__(256) void wgrad_plan_kernel(const int32_t* __restri
     virt_w2[s] = s * rows_w2;
     virt_w1[s] = s * rows_w1;
     if (s < S) {
-      kinfo[2 * s] = s_k[s];
-      kinfo[2 * s + 1] = s_k[s + 1] - s_k[s];
-      for (int i = s_k[s] / 64; i < s_k[s + 1] / 64; ++i) ktile_slot[i] = s;
+      long long a, b;
+      clip_slot(slot_offsets, s, P, &a, &b);
+      const int col0 = s_k[s], Ks = s_k[s + 1] - s_k[s];
+      kinfo[2 * s] = col0;
+      kinfo[2 * s + 1] = Ks;
+      for (int k0 = 0; k0 < Ks; k0 += 64) {
+        const long long r0 = a + k0 < b ? a + k0 : b;
+        ktile[(col0 + k0) / 64] = make_int4(int(r0), int(b), col0, Ks);
+      }
     }
   }
-  if (threadIdx.x == 0) ktile_slot[-1] = s_k[S] / 64;  // number of 64-column tiles in use
+  for (int i = s_k[S] / 64 + threadIdx.x; i < n_ktiles; i += blockDim.x) ktile[i] = make_int4(0, 0, 0, 0);
 }
 
-// src [P, C] -> per-slot blocks dst_s [C, K_s] at dst + C * col0_s, zero beyond the slot's rows.
-// One workgroup moves a 64 (rows) x 64 (columns) tile through LDS.
-__global__ __launch_bounds__(256) void transpose_pad_kernel(const uint16_t* __restrict__ src, int C,
-                                                            const int32_t* __restrict__ slot_offsets, long long P,
-                                                            const int32_t* __restrict__ kinfo,
-                                                            const int32_t* __restrict__ ktile_slot,
-                                                            uint16_t* __restrict__ dst) {
-  __shared__ uint16_t tile[64][64 + 2];
-  const int kt = blockIdx.x;
-  if (kt >= ktile_slot[-1]) return;
-  const int s = ktile_slot[kt];
-  const int col0 = kinfo[2 * s], Ks = kinfo[2 * s + 1];
-  long long a, b;
-  clip_slot(slot_offsets, s, P, &a, &b);
-  const int k0 = kt * 64 - col0;  // first row of the slot this tile covers
-  const int c0 = blockIdx.y * 64;
-  // read: 64 rows x 8 pieces of 8 columns
+// 64 rows [row0, row0 + 64) of a row-major matrix with C columns (rows >= row_end read as zero),
+// columns [c0, c0 + 256) -> dst[(c0 + c) * ld + j], j = 0..63: a 64 x 256 tile through LDS.
+// In: 512 contiguous bytes per row.  Out: a wave writes one 16-byte piece of 64 consecutive
+// dst rows per store (conflict-free LDS reads); the 8 pieces of a row complete its 128-byte line.
+constexpr int kTrCols = 256;
+constexpr int kTrPitch = kTrCols + 8;  // elements; keeps 16-byte alignment of the row-major writes
+__device__ __forceinline__ void transpose_tile(const uint16_t* __restrict__ src, long long row0, long long row_end,
+                                               int C, int c0, uint16_t* __restrict__ dst, long long ld,
+                                               uint16_t* tile) {
+  u32x4 in[8];
 #pragma unroll
-  for (int it = 0; it < 2; ++it) {
+  for (int it = 0; it < 8; ++it) {
     const int idx = it * 256 + threadIdx.x;
-    const int r = idx / 8, piece = idx % 8;
-    const long long row = a + k0 + r;
-    u32x4 v = {0u, 0u, 0u, 0u};
-    if (row < b) v = __builtin_nontemporal_load((const u32x4*)(src + (size_t)row * C + c0 + piece * 8));
-    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+    const int r = idx / 32, col = c0 + (idx % 32) * 8;
+    in[it] = u32x4{0u, 0u, 0u, 0u};
+    if (row0 + r < row_end && col < C) in[it] = *(const u32x4*)(src + (size_t)(row0 + r) * C + col);
+  }
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      tile[r][piece * 8 + 2 * q] = uint16_t(w[q] & 0xFFFFu);
-      tile[r][piece * 8 + 2 * q + 1] = uint16_t(w[q] >> 16);
-    }
+  for (int it = 0; it < 8; ++it) {
+    const int idx = it * 256 + threadIdx.x;
+    *(u32x4*)(tile + (idx / 32) * kTrPitch + (idx % 32) * 8) = in[it];
   }
   __syncthreads();
-  // write: 64 columns (rows of dst) x 8 pieces of 8 k-values
-  uint16_t* const block = dst + (size_t)C * col0;
 #pragma unroll
-  for (int it = 0; it < 2; ++it) {
+  for (int it = 0; it < 8; ++it) {
     const int idx = it * 256 + threadIdx.x;
-    const int c = idx % 64, piece = idx / 64;
+    const int c = idx % 256, piece = idx / 256;  // piece is uniform over the workgroup
+    if (c0 + c >= C) continue;
     uint32_t w[4];
 #pragma unroll
     for (int q = 0; q < 4; ++q)
-      w[q] = uint32_t(tile[piece * 8 + 2 * q][c]) | (uint32_t(tile[piece * 8 + 2 * q + 1][c]) << 16);
-    u32x4 v;
-    v.x = w[0];
-    v.y = w[1];
-    v.z = w[2];
-    v.w = w[3];
-    __builtin_nontemporal_store(v, (u32x4*)(block + (size_t)(c0 + c) * Ks + k0 + piece * 8));
+      w[q] = uint32_t(tile[(piece * 8 + 2 * q) * kTrPitch + c]) |
+             (uint32_t(tile[(piece * 8 + 2 * q + 1) * kTrPitch + c]) << 16);
+    *(u32x4*)(dst + (size_t)(c0 + c) * ld + piece * 8) = u32x4{w[0], w[1], w[2], w[3]};
   }
+}
+
+// src [P, C] -> per-slot blocks dst_s [C, K_s] at dst + C * col0_s, zero beyond the slot's rows
+__global__ __launch_bounds__(256) void transpose_pad_kernel(const uint16_t* __restrict__ src, int C,
+                                                            const int4* __restrict__ ktile,
+                                                            uint16_t* __restrict__ dst) {
+  __shared__ __attribute__((aligned(16))) uint16_t tile[64 * kTrPitch];
+  const int4 kt = ktile[blockIdx.x];  // {first row, end row, col0, K_s}
+  if (kt.w == 0) return;
+  const int k0 = blockIdx.x * 64 - kt.z;
+  transpose_tile(src, kt.x, kt.y, C, blockIdx.y * kTrCols, dst + (size_t)C * kt.z + k0, kt.w, tile);
 }
 
 // Batched transpose of whole weight matrices: src [S, R, C] -> dst [S, C, R], R and C multiples of 64.
 __global__ __launch_bounds__(256) void transpose_weights_kernel(const uint16_t* __restrict__ src, int R, int C,
                                                                 uint16_t* __restrict__ dst) {
-  __shared__ uint16_t tile[64][64 + 2];
+  __shared__ __attribute__((aligned(16))) uint16_t tile[64 * kTrPitch];
   const size_t base = (size_t)blockIdx.z * R * C;
-  const int r0 = blockIdx.x * 64, c0 = blockIdx.y * 64;
-#pragma unroll
-  for (int it = 0; it < 2; ++it) {
-    const int idx = it * 256 + threadIdx.x;
-    const int r = idx / 8, piece = idx % 8;
-    const u32x4 v = *(const u32x4*)(src + base + (size_t)(r0 + r) * C + c0 + piece * 8);
-    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
-#pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      tile[r][piece * 8 + 2 * q] = uint16_t(w[q] & 0xFFFFu);
-      tile[r][piece * 8 + 2 * q + 1] = uint16_t(w[q] >> 16);
-    }
-  }
-  __syncthreads();
-#pragma unroll
-  for (int it = 0; it < 2; ++it) {
-    const int idx = it * 256 + threadIdx.x;
-    const int c = idx % 64, piece = idx / 64;
-    u32x4 v;
-    uint32_t w[4];
-#pragma unroll
-    for (int q = 0; q < 4; ++q)
-      w[q] = uint32_t(tile[piece * 8 + 2 * q][c]) | (uint32_t(tile[piece * 8 + 2 * q + 1][c]) << 16);
-    v.x = w[0];
-    v.y = w[1];
-    v.z = w[2];
-    v.w = w[3];
-    *(u32x4*)(dst + base + (size_t)(c0 + c) * R + r0 + piece * 8) = v;
-  }
+  const int r0 = blockIdx.x * 64;
+  transpose_tile(src + base, r0, R, C, blockIdx.y * kTrCols, dst + base + r0, R, tile);
 }
 
 // dW[e] = sum over slots s with slot_expert[s] == e of dW_slot[s], ascending s, fp32 sum, one rounding
@@ -349,7 +326,7 @@ struct TrainWorkspace {
   uint16_t* ta;        // transposed left operand of a wgrad:  max(d, n1) x Kpad
   uint16_t* tb;        // transposed right operand:            max(ffn, d) x Kpad
   int32_t* kinfo;      // [2S]
-  int32_t* ktile_slot; // [1 + Kpad/64]; entry -1 = tiles in use
+  int4* ktile;         // [Kpad/64]
   int32_t* virt_w2;    // [S+1]
   int32_t* virt_w1;    // [S+1]
   void* tiles_fwd;     // rows of the batch: lists for n1 / 256 and d / 256 column tiles
@@ -380,7 +357,7 @@ TrainWorkspace carve_train(void* ws, const lz_shape* s) {
   w.ta = (uint16_t*)take((size_t)(s->d > w.n1 ? s->d : w.n1) * w.Kpad * 2);
   w.tb = (uint16_t*)take((size_t)(s->d > s->ffn ? s->d : s->ffn) * w.Kpad * 2);
   w.kinfo = (int32_t*)take(sizeof(int32_t) * 2 * S);
-  w.ktile_slot = (int32_t*)take(sizeof(int32_t) * (size_t)(w.Kpad / 64 + 64)) + 1;
+  w.ktile = (int4*)take(sizeof(int4) * (size_t)(w.Kpad / 64));
   w.virt_w2 = (int32_t*)take(sizeof(int32_t) * (S + 1));
   w.virt_w1 = (int32_t*)take(sizeof(int32_t) * (S + 1));
   w.tiles_fwd = take(tile_table_bytes(P, S, BM, kGroupM, ceil_div(w.n1, BN), s->d / BN));
@@ -451,11 +428,9 @@ int32_t gemm_wgrad(const uint16_t* At, const uint16_t* Wt, uint16_t* C, int S, i
   return launch_mfma<EPI_NONE, true>(g, st);
 }
 
-int32_t transpose_pad(const void* src, int C, const int32_t* slot_offsets, long long P, const TrainWorkspace& w,
-                      uint16_t* dst, hipStream_t st) {
-  const dim3 grid((unsigned)(w.Kpad / 64), (unsigned)(C / 64));
-  hipLaunchKernelGGL(transpose_pad_kernel, grid, dim3(256), 0, st, (const uint16_t*)src, C, slot_offsets, P,
-                     w.kinfo, w.ktile_slot, dst);
+int32_t transpose_pad(const void* src, int C, const TrainWorkspace& w, uint16_t* dst, hipStream_t st) {
+  const dim3 grid((unsigned)(w.Kpad / 64), (unsigned)ceil_div(C, kTrCols));
+  hipLaunchKernelGGL(transpose_pad_kernel, grid, dim3(256), 0, st, (const uint16_t*)src, C, w.ktile, dst);
   return lz::launch_status();
 }
 
@@ -472,7 +447,7 @@ extern "C" int32_t lz_transpose_weights(const void* w, int32_t S, int32_t rows, 
   if (S == 0) return LZ_OK;
   if (!w || !wt || !aligned16(w) || !aligned16(wt)) return LZ_EINVAL;
   if (S > 65535 || cols / 64 > 65535) return LZ_ESHAPE;
-  hipLaunchKernelGGL(transpose_weights_kernel, dim3(rows / 64, cols / 64, S), dim3(256), 0, (hipStream_t)stream,
+  hipLaunchKernelGGL(transpose_weights_kernel, dim3(rows / 64, ceil_div(cols, kTrCols), S), dim3(256), 0, (hipStream_t)stream,
                      (const uint16_t*)w, rows, cols, (uint16_t*)wt);
   return lz::launch_status();
 }
@@ -552,8 +527,8 @@ extern "C" int32_t lz_ffn_backward(const void* dyp, const void* xp, const void* 
   const int d = shape->d, ffn = shape->ffn, n1 = w.n1;
   const bool swiglu = shape->act == LZ_SWIGLU;
 
-  hipLaunchKernelGGL(wgrad_plan_kernel, dim3(1), dim3(256), 0, st, slot_offsets, S, P, d, n1, w.kinfo, w.ktile_slot,
-                     w.virt_w2, w.virt_w1);
+  hipLaunchKernelGGL(wgrad_plan_kernel, dim3(1), dim3(256), 0, st, slot_offsets, S, P, d, n1, int(w.Kpad / 64), w.kinfo,
+                     w.ktile, w.virt_w2, w.virt_w1);
   int32_t r = lz::launch_status();
   if (r != LZ_OK) return r;
   TileTable t_rows, t_w2, t_w1;
@@ -578,12 +553,12 @@ extern "C" int32_t lz_ffn_backward(const void* dyp, const void* xp, const void* 
     if ((r = gemm_rows(w.dz, (const uint16_t*)w1t, (uint16_t*)dxp, P, n1, d, 1, t_rows, st)) != LZ_OK) return r;
   }
   // dW2[s] = dyp_s^T H_s
-  if ((r = transpose_pad(dyp, d, slot_offsets, P, w, w.ta, st)) != LZ_OK) return r;
-  if ((r = transpose_pad(h, ffn, slot_offsets, P, w, w.tb, st)) != LZ_OK) return r;
+  if ((r = transpose_pad(dyp, d, w, w.ta, st)) != LZ_OK) return r;
+  if ((r = transpose_pad(h, ffn, w, w.tb, st)) != LZ_OK) return r;
   if ((r = gemm_wgrad(w.ta, w.tb, (uint16_t*)dw2, S, d, ffn, w.kinfo, t_w2, st)) != LZ_OK) return r;
   // dW1[s] = dZ_s^T xp_s
-  if ((r = transpose_pad(w.dz, n1, slot_offsets, P, w, w.ta, st)) != LZ_OK) return r;
-  if ((r = transpose_pad(xp, d, slot_offsets, P, w, w.tb, st)) != LZ_OK) return r;
+  if ((r = transpose_pad(w.dz, n1, w, w.ta, st)) != LZ_OK) return r;
+  if ((r = transpose_pad(xp, d, w, w.tb, st)) != LZ_OK) return r;
   return gemm_wgrad(w.ta, w.tb, (uint16_t*)dw1, S, n1, d, w.kinfo, t_w1, st);
 }
 
