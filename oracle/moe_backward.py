@@ -72,6 +72,17 @@ def act_backward(dH: np.ndarray, Z: np.ndarray, act: str) -> np.ndarray:
     return np.concatenate([dH * U * silu_grad(G), dH * silu(G)], axis=1)
 
 
+def ffn_backward_slot(dYp, Xp, W1, W2, act):
+    """Backward of one slot's FFN on its rows (all fp64): returns (dxp, dw1, dw2)."""
+    Z = Xp @ W1.T
+    H = act_forward(Z, act)
+    dH = dYp @ W2
+    dw2 = dYp.T @ H
+    dZ = act_backward(dH, Z, act)
+    dw1 = dZ.T @ Xp
+    return dZ @ W1, dw1, dw2
+
+
 def ffn_backward_rows(dyp, xp, slot_offsets, slot_expert, w1, w2, act):
     """Backward of the per-slot FFN.  w1 / w2 are indexed by expert.  Returns
     (dxp [P,d], dw1_slot [S,n1,d], dw2_slot [S,d,ffn]): every slot's own weight gradient
@@ -89,14 +100,7 @@ def ffn_backward_rows(dyp, xp, slot_offsets, slot_expert, w1, w2, act):
         if b <= a:
             continue
         e = int(slot_expert[s])
-        W1, W2 = widen(w1[e]), widen(w2[e])
-        Z = Xp[a:b] @ W1.T
-        H = act_forward(Z, act)
-        dH = dYp[a:b] @ W2
-        dw2[s] = dYp[a:b].T @ H
-        dZ = act_backward(dH, Z, act)
-        dw1[s] = dZ.T @ Xp[a:b]
-        dxp[a:b] = dZ @ W1
+        dxp[a:b], dw1[s], dw2[s] = ffn_backward_slot(dYp[a:b], Xp[a:b], widen(w1[e]), widen(w2[e]), act)
     return dxp, dw1, dw2
 
 

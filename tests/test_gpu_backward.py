@@ -172,6 +172,61 @@ def test_layer_backward_end_to_end(act):
         assert torch.equal(a.view(torch.int16), b.view(torch.int16))
 
 
+@pytest.mark.parametrize("name", ["c3_gptmoe", "c4_finegrained"])
+def test_full_config_backward(name):
+    """Full size, in the launch configuration the timing runs use: the largest, the smallest
+    non-empty, a middle and an empty slot are checked completely (dxp rows, both weight
+    gradients) against the fp64 oracle; the streaming steps on all rows from the device's own
+    inputs."""
+    cfg = CONFIGS[name]
+    w = expert_weights(cfg, threads=16)
+    inp = step_inputs(cfg, 0)
+    ids, gates = om.route(inp["logits"], cfg.k)
+    plan = oracle_plan(cfg, ids)
+    disp = om.plan_dispatch(ids, inp["rank_tok_off"], plan, cfg.E, cfg.N, cfg.c)
+    shape = lz.Shape.from_config(cfg)
+    layer = lz.MoELayer(shape, DEV)
+    layer.load_expert_weights(w["w1"], w["w2"], plan)
+    layer.set_plan(plan, inp["rank_tok_off"])
+    layer.enable_training()
+    dy = _bf16(np.random.default_rng(21), (cfg.T, cfg.d))
+    layer.forward_train(to_dev(inp["logits"]), to_dev(inp["x"], True))
+    layer.backward(to_dev(dy, True))
+    torch.cuda.synchronize()
+    assert np.array_equal(to_host(layer.pair_to_row), disp["pair_to_row"])
+    off, counts = disp["slot_offsets"], disp["slot_counts"]
+    # combine backward on all rows, from the device's own yp
+    yp_dev = to_host(layer.yp)
+    dyp_ref, dg_ref = ob.combine_backward(dy, yp_dev, disp["pair_to_row"], to_host(layer.topk_gates))
+    dyp_dev = to_host(layer.dyp)
+    assert np.all(np.abs(om.widen(dyp_dev) - dyp_ref) <= 0.006 * np.abs(dyp_ref))
+    assert np.allclose(to_host(layer.dgates), dg_ref, rtol=1e-4, atol=1e-4 * np.max(np.abs(dg_ref)))
+    # slots checked completely
+    nz = np.nonzero(counts)[0]
+    order = nz[np.argsort(counts[nz])]
+    chosen = [int(order[0]), int(order[len(order) // 2]), int(order[-1])]
+    xp_dev, dxp_dev = to_host(layer.xp), to_host(layer.dxp)
+    for s in chosen:
+        a, b = off[s], off[s + 1]
+        e = int(plan[s])
+        dxp_ref, dw1_ref, dw2_ref = ob.ffn_backward_slot(om.widen(dyp_dev[a:b]), om.widen(xp_dev[a:b]),
+                                                        om.widen(w["w1"][e]), om.widen(w["w2"][e]), cfg.act)
+        assert rel_err(dxp_dev[a:b], dxp_ref) <= TOL, (s, "dxp")
+        assert rel_err(to_host(layer.dw1_slot[s]), dw1_ref) <= TOL, (s, "dw1")
+        assert rel_err(to_host(layer.dw2_slot[s]), dw2_ref) <= TOL, (s, "dw2")
+    for s in np.nonzero(counts == 0)[0][:2]:
+        assert not layer.dw1_slot[int(s)].any().item() and not layer.dw2_slot[int(s)].any().item()
+    # permute backward on all tokens from the device's own dxp; replica sums for one expert
+    dx_ref = ob.permute_backward(dxp_dev, disp["pair_to_row"], cfg.k)
+    assert np.all(np.abs(om.widen(to_host(layer.dx)) - dx_ref) <= 0.006 * np.abs(dx_ref) + 1e-6)
+    e = int(plan[chosen[-1]])
+    slots = [s for s in range(cfg.N * cfg.c) if plan[s] == e]
+    ref = sum(om.widen(to_host(layer.dw2_slot[s])) for s in slots)
+    assert np.all(np.abs(om.widen(to_host(layer.dw2[e])) - ref) <= 0.006 * np.abs(ref) + 1e-6)
+    dl_ref = ob.route_backward(to_host(layer.dgates), to_host(layer.topk_gates), ids, cfg.E)
+    assert np.allclose(to_host(layer.dlogits), dl_ref, rtol=1e-4, atol=1e-5 * np.max(np.abs(dl_ref)))
+
+
 def test_training_entry_points_reject_what_they_do_not_serve():
     f32 = lz.Shape.from_config(CONFIGS["c1_tiny"])
     assert lz.lz_train_workspace_bytes(f32) == 0
