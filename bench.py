@@ -124,6 +124,65 @@ def replan_latency(torch, lz, dev):
     return out
 
 
+def training_pass(torch, lz, layer, cfg, logits, x, iters=5):
+    """Forward that keeps its intermediates plus the backward chain on the same layer object,
+    every call timed by an event pair (median of `iters`); reported beside the headline, not in it."""
+    s = layer.shape
+    if lz.lz_train_workspace_bytes(s) == 0:
+        return None
+    layer.enable_training()
+    dy = torch.randn((s.T, s.d), device=layer.device).to(torch.bfloat16)
+    n1 = layer.w1.shape[1]
+    P, S = s.P, s.S
+
+    def reduce():
+        lz.lz_reduce_replica_grads(layer.dw1_slot, layer.slot_expert, S, s.E, layer.dw1_slot[0].numel(), layer.dw1)
+        lz.lz_reduce_replica_grads(layer.dw2_slot, layer.slot_expert, S, s.E, layer.dw2_slot[0].numel(), layer.dw2)
+
+    calls = [
+        ("forward_train", lambda: layer.forward_train(logits, x)),
+        ("weight_transposes", layer.refresh_weight_transposes),
+        ("combine_backward", lambda: lz.lz_combine_backward(dy, layer.yp, layer.pair_to_row, layer.topk_gates, s,
+                                                            layer.dyp, layer.dgates)),
+        ("ffn_backward", lambda: lz.lz_ffn_backward(layer.dyp, layer.xp, layer.z, layer.h, layer.slot_offsets,
+                                                    layer.w1t, layer.w2t, s, layer.dxp, layer.dw1_slot,
+                                                    layer.dw2_slot, layer.train_ws, layer.train_ws_bytes)),
+        ("permute_backward", lambda: lz.lz_permute_backward(layer.dxp, layer.pair_to_row, s, layer.dx)),
+        ("route_backward", lambda: lz.lz_route_backward(layer.dgates, layer.topk_gates, layer.topk_ids, s,
+                                                        layer.dlogits)),
+        ("reduce_replica_grads", reduce),
+    ]
+    ms = {}
+    for name, fn in calls:
+        fn()
+        torch.cuda.synchronize()
+        pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(iters)]
+        for a, b in pairs:
+            a.record()
+            fn()
+            b.record()
+        torch.cuda.synchronize()
+        ms[name] = float(np.median([a.elapsed_time(b) for a, b in pairs]))
+    flops_fwd = 2.0 * P * s.d * (n1 + s.ffn)
+    backward_ms = sum(v for k, v in ms.items() if k not in ("forward_train", "weight_transposes"))
+    w_elems = S * (n1 + s.ffn) * s.d
+    return {
+        "ms": ms,
+        "backward_ms": backward_ms,
+        "forward_plus_backward_ms": ms["forward_train"] + backward_ms,
+        "tokens_per_s_forward_plus_backward": s.T / ((ms["forward_train"] + backward_ms) * 1e-3),
+        "ffn_backward_TFLOPs": 2 * flops_fwd / (ms["ffn_backward"] * 1e-3) / 1e12,
+        "ffn_backward_frac_mfma_peak": 2 * flops_fwd / (ms["ffn_backward"] * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+        "forward_train_TFLOPs": flops_fwd / (ms["forward_train"] * 1e-3) / 1e12,
+        "combine_backward_GBps": 2.0 * (s.T + 2 * P) * s.d / (ms["combine_backward"] * 1e-3) / 1e9,
+        "reduce_replica_grads_GBps": 2.0 * (S + s.E) * (n1 + s.ffn) * s.d / (ms["reduce_replica_grads"] * 1e-3) / 1e9,
+        "weight_transposes_GBps": 4.0 * w_elems / (ms["weight_transposes"] * 1e-3) / 1e9,
+        "note": "ffn_backward = two dgrad and two wgrad grouped GEMMs (4 * P * d * (n1 + ffn) flops on real rows), "
+                "the activation backward and the slot-wise transposes of the wgrad operands; weight_transposes "
+                "is the once-per-optimizer-step refresh of the transposed weight copies (not in backward_ms)",
+    }
+
+
 def cpu_baseline(cfg, inp, w, plan_fn, n_tokens):
     """The oracle, as it stands, over the first n_tokens tokens of the batch: routing,
     dispatch schedule + row maps, permute, per-slot fp64 FFN, combine."""
@@ -372,6 +431,8 @@ def main():
         out["derived"]["permute_GBps_cold"] = permute_bytes / (cold_ms["permute"] * 1e-3) / 1e9
         out["derived"]["combine_GBps_cold"] = combine_bytes / (cold_ms["combine"] * 1e-3) / 1e9
     if not args.no_extras:
+        if bf16:
+            out["training"] = training_pass(torch, lz, layer, cfg, logits, x)
         del layer, x
         torch.cuda.empty_cache()
         out["achievable"] = achievable_peaks(torch, dev)
