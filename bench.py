@@ -141,11 +141,10 @@ def training_pass(torch, lz, layer, cfg, logits, x, iters=5):
 
     calls = [
         ("forward_train", lambda: layer.forward_train(logits, x)),
-        ("weight_transposes", layer.refresh_weight_transposes),
         ("combine_backward", lambda: lz.lz_combine_backward(dy, layer.yp, layer.pair_to_row, layer.topk_gates, s,
                                                             layer.dyp, layer.dgates)),
         ("ffn_backward", lambda: lz.lz_ffn_backward(layer.dyp, layer.xp, layer.z, layer.h, layer.slot_offsets,
-                                                    layer.w1t, layer.w2t, s, layer.dxp, layer.dw1_slot,
+                                                    layer.w1, layer.w2, s, layer.dxp, layer.dw1_slot,
                                                     layer.dw2_slot, layer.train_ws, layer.train_ws_bytes)),
         ("permute_backward", lambda: lz.lz_permute_backward(layer.dxp, layer.pair_to_row, s, layer.dx)),
         ("route_backward", lambda: lz.lz_route_backward(layer.dgates, layer.topk_gates, layer.topk_ids, s,
@@ -164,8 +163,7 @@ def training_pass(torch, lz, layer, cfg, logits, x, iters=5):
         torch.cuda.synchronize()
         ms[name] = float(np.median([a.elapsed_time(b) for a, b in pairs]))
     flops_fwd = 2.0 * P * s.d * (n1 + s.ffn)
-    backward_ms = sum(v for k, v in ms.items() if k not in ("forward_train", "weight_transposes"))
-    w_elems = S * (n1 + s.ffn) * s.d
+    backward_ms = sum(v for k, v in ms.items() if k != "forward_train")
     return {
         "ms": ms,
         "backward_ms": backward_ms,
@@ -176,10 +174,8 @@ def training_pass(torch, lz, layer, cfg, logits, x, iters=5):
         "forward_train_TFLOPs": flops_fwd / (ms["forward_train"] * 1e-3) / 1e12,
         "combine_backward_GBps": 2.0 * (s.T + 2 * P) * s.d / (ms["combine_backward"] * 1e-3) / 1e9,
         "reduce_replica_grads_GBps": 2.0 * (S + s.E) * (n1 + s.ffn) * s.d / (ms["reduce_replica_grads"] * 1e-3) / 1e9,
-        "weight_transposes_GBps": 4.0 * w_elems / (ms["weight_transposes"] * 1e-3) / 1e9,
-        "note": "ffn_backward = two dgrad and two wgrad grouped GEMMs (4 * P * d * (n1 + ffn) flops on real rows), "
-                "the activation backward and the slot-wise transposes of the wgrad operands; weight_transposes "
-                "is the once-per-optimizer-step refresh of the transposed weight copies (not in backward_ms)",
+        "note": "ffn_backward = two dgrad and two wgrad grouped GEMMs (4 * P * d * (n1 + ffn) flops on real rows) "
+                "and the activation backward",
     }
 
 

@@ -190,20 +190,15 @@ int32_t lz_unpermute_combine(const void* yp, const int32_t* pair_to_row,
  *
  * bf16 tensors only (LZ_ESHAPE otherwise), products accumulated in fp32, every stored tensor
  * rounded to bf16 once.  The FFN calls need d % 256 == 0, ffn % 64 == 0, d*ffn*4 < 2^31,
- * T*k <= 2^22 and N*c*max(d, 2*ffn) < 2^31.  All tensor pointers are device memory, 16-byte
+ * T*k*max(d, 2*ffn)*2 < 2^31 and N*c*max(d, 2*ffn) < 2^31.  All tensor pointers are device memory, 16-byte
  * aligned; `ws` is 256-byte aligned device memory of lz_train_workspace_bytes(shape) bytes that
  * serves one call at a time. */
 size_t lz_train_workspace_bytes(const lz_shape* shape);
 
-/* wt[s] = w[s]^T for s < S: w dev [S, rows, cols] -> wt dev [S, cols, rows], bf16, rows and
- * cols multiples of 64.  lz_ffn_backward contracts over the rows of a weight matrix, and the
- * MFMA kernel wants its operands contiguous along the contraction: the caller keeps these
- * transposes beside the weights and refreshes them when the weights change. */
-int32_t lz_transpose_weights(const void* w, int32_t S, int32_t rows, int32_t cols, void* wt, void* stream);
-
 /* lz_expert_ffn that also returns what the backward needs: z = xp W1^T (pre-activation,
  * [P, n1]; SwiGLU: columns [0,ffn) gate, [ffn,2ffn) up) and h = act(z) [P, ffn].  The
- * activation is applied to the bf16-rounded z.  Rows outside every slot are left untouched.
+ * activation is applied to the bf16-rounded z.  Rows of z and yp outside every slot are left
+ * untouched, such rows of h are unspecified.
  *   xp dev [P,d], w1 dev [S,n1,d], w2 dev [S,d,ffn], z dev [P,n1] out, h dev [P,ffn] out, yp dev [P,d] out */
 int32_t lz_ffn_forward_train(const void* xp, const int32_t* slot_offsets, const void* w1, const void* w2,
                              const lz_shape* shape, void* z, void* h, void* yp, void* ws, size_t ws_bytes,
@@ -217,11 +212,11 @@ int32_t lz_combine_backward(const void* dy, const void* yp, const int32_t* pair_
 
 /* Backward of the expert FFN over the permuted buffer.
  *   dyp, xp dev [P,d]; z dev [P,n1], h dev [P,ffn] from lz_ffn_forward_train
- *   w1t dev [S,d,n1] = transposes of w1, w2t dev [S,ffn,d] = transposes of w2
+ *   w1 dev [S,n1,d], w2 dev [S,d,ffn]: the forward's weights, as they are
  *   dxp dev [P,d] out (rows outside every slot untouched)
  *   dw1 dev [S,n1,d] out, dw2 dev [S,d,ffn] out: each slot's own gradient, zero for an empty slot */
 int32_t lz_ffn_backward(const void* dyp, const void* xp, const void* z, const void* h,
-                        const int32_t* slot_offsets, const void* w1t, const void* w2t,
+                        const int32_t* slot_offsets, const void* w1, const void* w2,
                         const lz_shape* shape, void* dxp, void* dw1, void* dw2, void* ws,
                         size_t ws_bytes, void* stream);
 

@@ -13,7 +13,7 @@ __all__ = [
     "lz_route", "lz_plan_dispatch", "lz_permute", "lz_permute_scatter", "lz_expert_ffn", "lz_unpermute_combine",
     "lz_ffn_tiles", "lz_ffn_up", "lz_ffn_down", "lz_allocate_replicas", "lz_place_mro", "lz_place_spread", "lz_place_compact", "lz_recovery_probability",
     "lz_replan", "lz_apply_transfers", "MoELayer",
-    "lz_train_workspace_bytes", "lz_transpose_weights", "lz_ffn_forward_train", "lz_combine_backward",
+    "lz_train_workspace_bytes", "lz_ffn_forward_train", "lz_combine_backward",
     "lz_ffn_backward", "lz_permute_backward", "lz_route_backward", "lz_reduce_replica_grads",
 ]
 
@@ -112,7 +112,6 @@ def _load():
         "lz_replan": (i32, [vp, i32, i32, vp, vp, i32, i32, i32, vp, vp, vp, vp, vp]),
         "lz_apply_transfers": (i32, [vp, i32, vp, vp, i32, vp, vp, i32, sp, vp]),
         "lz_train_workspace_bytes": (u64, [sp]),
-        "lz_transpose_weights": (i32, [vp, i32, i32, i32, vp, vp]),
         "lz_ffn_forward_train": (i32, [vp, vp, vp, vp, sp, vp, vp, vp, vp, u64, vp]),
         "lz_combine_backward": (i32, [vp, vp, vp, vp, sp, vp, vp, vp]),
         "lz_ffn_backward": (i32, [vp, vp, vp, vp, vp, vp, vp, sp, vp, vp, vp, vp, u64, vp]),
@@ -221,11 +220,6 @@ def lz_train_workspace_bytes(shape: Shape) -> int:
     return int(lib.lz_train_workspace_bytes(C.byref(shape.c_struct())))
 
 
-def lz_transpose_weights(w, S, rows, cols, wt, stream=None):
-    _check(lib.lz_transpose_weights(_ptr(w), S, rows, cols, _ptr(wt),
-                                    _stream() if stream is None else stream), "lz_transpose_weights")
-
-
 def lz_ffn_forward_train(xp, slot_offsets, w1, w2, shape, z, h, yp, ws, ws_bytes, stream=None):
     _check(lib.lz_ffn_forward_train(_ptr(xp), _ptr(slot_offsets), _ptr(w1), _ptr(w2), C.byref(shape.c_struct()),
                                     _ptr(z), _ptr(h), _ptr(yp), _ptr(ws), ws_bytes,
@@ -238,8 +232,8 @@ def lz_combine_backward(dy, yp, pair_to_row, topk_gates, shape, dyp, dgates, str
                                    _stream() if stream is None else stream), "lz_combine_backward")
 
 
-def lz_ffn_backward(dyp, xp, z, h, slot_offsets, w1t, w2t, shape, dxp, dw1, dw2, ws, ws_bytes, stream=None):
-    _check(lib.lz_ffn_backward(_ptr(dyp), _ptr(xp), _ptr(z), _ptr(h), _ptr(slot_offsets), _ptr(w1t), _ptr(w2t),
+def lz_ffn_backward(dyp, xp, z, h, slot_offsets, w1, w2, shape, dxp, dw1, dw2, ws, ws_bytes, stream=None):
+    _check(lib.lz_ffn_backward(_ptr(dyp), _ptr(xp), _ptr(z), _ptr(h), _ptr(slot_offsets), _ptr(w1), _ptr(w2),
                                C.byref(shape.c_struct()), _ptr(dxp), _ptr(dw1), _ptr(dw2), _ptr(ws), ws_bytes,
                                _stream() if stream is None else stream), "lz_ffn_backward")
 
@@ -428,7 +422,7 @@ class MoELayer:
 
     # ---- training: forward that keeps its intermediates, then the backward chain
     def enable_training(self):
-        """Allocate what the backward needs (bf16 MFMA shapes only) and transpose the weights."""
+        """Allocate what the backward needs (bf16 MFMA shapes only)."""
         import torch
         s, dev = self.shape, self.device
         bf = torch.bfloat16
@@ -448,14 +442,6 @@ class MoELayer:
         self.dw2_slot = torch.empty((s.S, s.d, s.ffn), dtype=bf, device=dev)
         self.dw1 = torch.empty((s.E, n1, s.d), dtype=bf, device=dev)
         self.dw2 = torch.empty((s.E, s.d, s.ffn), dtype=bf, device=dev)
-        self.w1t = torch.empty((s.S, s.d, n1), dtype=bf, device=dev)
-        self.w2t = torch.empty((s.S, s.ffn, s.d), dtype=bf, device=dev)
-        self.refresh_weight_transposes()
-
-    def refresh_weight_transposes(self):
-        s = self.shape
-        lz_transpose_weights(self.w1, s.S, self.w1.shape[1], s.d, self.w1t)
-        lz_transpose_weights(self.w2, s.S, s.d, s.ffn, self.w2t)
 
     def forward_train(self, logits, x):
         self.route(logits)
@@ -469,7 +455,7 @@ class MoELayer:
     def backward(self, dy):
         s = self.shape
         lz_combine_backward(dy, self.yp, self.pair_to_row, self.topk_gates, s, self.dyp, self.dgates)
-        lz_ffn_backward(self.dyp, self.xp, self.z, self.h, self.slot_offsets, self.w1t, self.w2t, s, self.dxp,
+        lz_ffn_backward(self.dyp, self.xp, self.z, self.h, self.slot_offsets, self.w1, self.w2, s, self.dxp,
                         self.dw1_slot, self.dw2_slot, self.train_ws, self.train_ws_bytes)
         lz_permute_backward(self.dxp, self.pair_to_row, s, self.dx)
         lz_route_backward(self.dgates, self.topk_gates, self.topk_ids, s, self.dlogits)

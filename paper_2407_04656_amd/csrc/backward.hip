@@ -10,13 +10,13 @@
 //   gate         dlogits = softmax backward on the k selected logits
 //   replicas     dW[e] = sum over the slots that hold e                             HBM streaming
 //
-// Every contraction runs on the forward's grouped MFMA kernel, which wants both operands
-// K-contiguous.  The dgrads contract over a weight matrix's rows, so they take the weights
-// transposed ([S, ffn, d] and [S, d, n1], kept beside the originals: HBM capacity is not what
-// limits this layer).  The wgrads contract over a slot's rows, a different length for every
-// slot: both operands are first transposed slot by slot into blocks [columns, K_s] with K_s the
-// slot's row count rounded up to 64 (at least 128) and zero filled, and the kernel runs in its
-// ragged-K mode over S x (rows of the weight matrix) virtual rows.
+// Every contraction runs on the forward's grouped MFMA kernel.  The data gradients contract
+// over a weight matrix's rows and the weight gradients over a slot's rows (a different length
+// for every slot), so one or both operands arrive with the contraction index as their slow
+// dimension: the kernel's k-major modes stream such tiles into LDS as they are and transpose
+// them on the way to the registers (gfx950's transposing LDS reads), so no transposed copy of
+// weights or activations is ever written.  The weight gradients run over S x (rows of the
+// weight matrix) virtual rows; each tile takes its contraction range from slot_offsets.
 #include "gemm_mfma.h"
 
 namespace {
@@ -194,109 +194,13 @@ __global__ __launch_bounds__(256) void act_backward_kernel(const u32x4* __restri
   }
 }
 
-// ---- ragged-K layout of the weight-gradient operands.
-// Slot s with R_s rows contracts over K_s = max(128, R_s rounded up to 64) columns, starting at
-// column col0_s = sum of the earlier K's: kinfo[2s] = col0_s, kinfo[2s+1] = K_s.  ktile[i]
-// describes the i-th 64-column tile of that layout for the transposing copy: {first source
-// row, end row of its slot, col0_s, K_s}, K_s = 0 for tiles past the last slot.  virt_w2 /
-// virt_w1 are the slot offsets of the S x rows_per_slot virtual rows of the two outputs.
-__global__ __launch_bounds__(256) void wgrad_plan_kernel(const int32_t* __restrict__ slot_offsets, int S, long long P,
-                                                         int rows_w2, int rows_w1, int n_ktiles,
-                                                         int32_t* __restrict__ kinfo, int4* __restrict__ ktile,
-                                                         int32_t* __restrict__ virt_w2,
-                                                         int32_t* __restrict__ virt_w1) {
-  __shared__ int s_k[lz::kMaxN * lz::kMaxC + 1];
-  for (int s = threadIdx.x; s < S; s += blockDim.x) {
-    long long a, b;
-    clip_slot(slot_offsets, s, P, &a, &b);
-    const int rows = int(b - a);
-    const int k = (rows + 63) / 64 * 64;
-    s_k[s + 1] = k < 128 ? 128 : k;
-  }
-  __syncthreads();
-  if (threadIdx.x == 0) {
-    int run = 0;
-    for (int s = 0; s < S; ++s) {
-      const int k = s_k[s + 1];
-      s_k[s] = run;
-      run += k;
-    }
-    s_k[S] = run;
-  }
-  __syncthreads();
+// slot offsets of the S x rows_per_slot virtual rows of the two weight-gradient outputs
+__global__ void virtual_rows_kernel(int S, int rows_w2, int rows_w1, int32_t* __restrict__ virt_w2,
+                                    int32_t* __restrict__ virt_w1) {
   for (int s = threadIdx.x; s <= S; s += blockDim.x) {
     virt_w2[s] = s * rows_w2;
     virt_w1[s] = s * rows_w1;
-    if (s < S) {
-      long long a, b;
-      clip_slot(slot_offsets, s, P, &a, &b);
-      const int col0 = s_k[s], Ks = s_k[s + 1] - s_k[s];
-      kinfo[2 * s] = col0;
-      kinfo[2 * s + 1] = Ks;
-      for (int k0 = 0; k0 < Ks; k0 += 64) {
-        const long long r0 = a + k0 < b ? a + k0 : b;
-        ktile[(col0 + k0) / 64] = make_int4(int(r0), int(b), col0, Ks);
-      }
-    }
   }
-  for (int i = s_k[S] / 64 + threadIdx.x; i < n_ktiles; i += blockDim.x) ktile[i] = make_int4(0, 0, 0, 0);
-}
-
-// 64 rows [row0, row0 + 64) of a row-major matrix with C columns (rows >= row_end read as zero),
-// columns [c0, c0 + 256) -> dst[(c0 + c) * ld + j], j = 0..63: a 64 x 256 tile through LDS.
-// In: 512 contiguous bytes per row.  Out: a wave writes one 16-byte piece of 64 consecutive
-// dst rows per store (conflict-free LDS reads); the 8 pieces of a row complete its 128-byte line.
-constexpr int kTrCols = 256;
-constexpr int kTrPitch = kTrCols + 8;  // elements; keeps 16-byte alignment of the row-major writes
-__device__ __forceinline__ void transpose_tile(const uint16_t* __restrict__ src, long long row0, long long row_end,
-                                               int C, int c0, uint16_t* __restrict__ dst, long long ld,
-                                               uint16_t* tile) {
-  u32x4 in[8];
-#pragma unroll
-  for (int it = 0; it < 8; ++it) {
-    const int idx = it * 256 + threadIdx.x;
-    const int r = idx / 32, col = c0 + (idx % 32) * 8;
-    in[it] = u32x4{0u, 0u, 0u, 0u};
-    if (row0 + r < row_end && col < C) in[it] = *(const u32x4*)(src + (size_t)(row0 + r) * C + col);
-  }
-#pragma unroll
-  for (int it = 0; it < 8; ++it) {
-    const int idx = it * 256 + threadIdx.x;
-    *(u32x4*)(tile + (idx / 32) * kTrPitch + (idx % 32) * 8) = in[it];
-  }
-  __syncthreads();
-#pragma unroll
-  for (int it = 0; it < 8; ++it) {
-    const int idx = it * 256 + threadIdx.x;
-    const int c = idx % 256, piece = idx / 256;  // piece is uniform over the workgroup
-    if (c0 + c >= C) continue;
-    uint32_t w[4];
-#pragma unroll
-    for (int q = 0; q < 4; ++q)
-      w[q] = uint32_t(tile[(piece * 8 + 2 * q) * kTrPitch + c]) |
-             (uint32_t(tile[(piece * 8 + 2 * q + 1) * kTrPitch + c]) << 16);
-    *(u32x4*)(dst + (size_t)(c0 + c) * ld + piece * 8) = u32x4{w[0], w[1], w[2], w[3]};
-  }
-}
-
-// src [P, C] -> per-slot blocks dst_s [C, K_s] at dst + C * col0_s, zero beyond the slot's rows
-__global__ __launch_bounds__(256) void transpose_pad_kernel(const uint16_t* __restrict__ src, int C,
-                                                            const int4* __restrict__ ktile,
-                                                            uint16_t* __restrict__ dst) {
-  __shared__ __attribute__((aligned(16))) uint16_t tile[64 * kTrPitch];
-  const int4 kt = ktile[blockIdx.x];  // {first row, end row, col0, K_s}
-  if (kt.w == 0) return;
-  const int k0 = blockIdx.x * 64 - kt.z;
-  transpose_tile(src, kt.x, kt.y, C, blockIdx.y * kTrCols, dst + (size_t)C * kt.z + k0, kt.w, tile);
-}
-
-// Batched transpose of whole weight matrices: src [S, R, C] -> dst [S, C, R], R and C multiples of 64.
-__global__ __launch_bounds__(256) void transpose_weights_kernel(const uint16_t* __restrict__ src, int R, int C,
-                                                                uint16_t* __restrict__ dst) {
-  __shared__ __attribute__((aligned(16))) uint16_t tile[64 * kTrPitch];
-  const size_t base = (size_t)blockIdx.z * R * C;
-  const int r0 = blockIdx.x * 64;
-  transpose_tile(src + base, r0, R, C, blockIdx.y * kTrCols, dst + base + r0, R, tile);
 }
 
 // dW[e] = sum over slots s with slot_expert[s] == e of dW_slot[s], ascending s, fp32 sum, one rounding
@@ -323,10 +227,6 @@ inline bool aligned16(const void* p) { return ((uintptr_t)p & 15) == 0; }
 struct TrainWorkspace {
   uint16_t* dh;        // [P, ffn]
   uint16_t* dz;        // [P, n1]
-  uint16_t* ta;        // transposed left operand of a wgrad:  max(d, n1) x Kpad
-  uint16_t* tb;        // transposed right operand:            max(ffn, d) x Kpad
-  int32_t* kinfo;      // [2S]
-  int4* ktile;         // [Kpad/64]
   int32_t* virt_w2;    // [S+1]
   int32_t* virt_w1;    // [S+1]
   void* tiles_fwd;     // rows of the batch: lists for n1 / 256 and d / 256 column tiles
@@ -334,7 +234,6 @@ struct TrainWorkspace {
   void* tiles_w2;      // S * d virtual rows, ffn / 256 column tiles
   void* tiles_w1;      // S * n1 virtual rows, d / 256 column tiles
   size_t total_bytes;
-  long long Kpad;
   int n1;
 };
 
@@ -345,7 +244,6 @@ TrainWorkspace carve_train(void* ws, const lz_shape* s) {
   const long long P = (long long)s->T * s->k;
   const int S = s->N * s->c;
   w.n1 = s->ffn * (s->act == LZ_SWIGLU ? 2 : 1);
-  w.Kpad = (P + 63) / 64 * 64 + 128ll * S;
   char* p = (char*)ws;
   auto take = [&](size_t bytes) {
     char* r = p;
@@ -354,10 +252,6 @@ TrainWorkspace carve_train(void* ws, const lz_shape* s) {
   };
   w.dh = (uint16_t*)take((size_t)P * s->ffn * 2);
   w.dz = (uint16_t*)take((size_t)P * w.n1 * 2);
-  w.ta = (uint16_t*)take((size_t)(s->d > w.n1 ? s->d : w.n1) * w.Kpad * 2);
-  w.tb = (uint16_t*)take((size_t)(s->d > s->ffn ? s->d : s->ffn) * w.Kpad * 2);
-  w.kinfo = (int32_t*)take(sizeof(int32_t) * 2 * S);
-  w.ktile = (int4*)take(sizeof(int4) * (size_t)(w.Kpad / 64));
   w.virt_w2 = (int32_t*)take(sizeof(int32_t) * (S + 1));
   w.virt_w1 = (int32_t*)take(sizeof(int32_t) * (S + 1));
   w.tiles_fwd = take(tile_table_bytes(P, S, BM, kGroupM, ceil_div(w.n1, BN), s->d / BN));
@@ -373,7 +267,8 @@ inline bool train_shape(const lz_shape* s) {
   if (!lz::shape_ok(s) || s->dtype != LZ_BF16) return false;
   if (s->d % BN != 0 || s->ffn % 64 != 0) return false;
   if ((long long)s->d * s->ffn * 4 >= (1ll << 31)) return false;
-  if ((long long)s->T * s->k > (1ll << 22)) return false;  // 256 rows of a slot's K stay below 2^31 bytes
+  // a slot's rows of a k-major operand are addressed with 32-bit byte offsets
+  if ((long long)s->T * s->k * (s->d > 2 * s->ffn ? s->d : 2 * s->ffn) * 2 >= (1ll << 31)) return false;
   const long long S = (long long)s->N * s->c;
   return S * s->d * 2 < (1ll << 31) && S * s->ffn * 2 < (1ll << 31);  // virtual row indices are int32
 }
@@ -409,29 +304,43 @@ int32_t gemm_rows(const uint16_t* A, const uint16_t* W, uint16_t* C, long long P
   return launch_mfma<EPI_NONE>(g, st);
 }
 
-// dW[s] [rows_per_slot, n_out] = A_s [rows_per_slot, K_s] W_s [n_out, K_s]^T
-int32_t gemm_wgrad(const uint16_t* At, const uint16_t* Wt, uint16_t* C, int S, int rows_per_slot, int n_out,
-                   const int32_t* kinfo, const TileTable& t, hipStream_t st) {
+// C[rows, n_out] = A[rows, K] W[slot][K, n_out] over the batch's ragged row ranges
+int32_t gemm_dgrad(const uint16_t* A, const uint16_t* W, uint16_t* C, long long P, int K, int n_out, int which,
+                   const TileTable& t, hipStream_t st) {
   MfmaArgs g{};
-  g.A = At;
-  g.W = Wt;
+  g.A = A;
+  g.W = W;
+  g.C = C;
+  g.P = P;
+  g.K = K;
+  g.w_rows = n_out;
+  g.n_out = n_out;
+  g.n_tiles = ceil_div(n_out, BN);
+  g.which = which;
+  g.t = t;
+  g.ldw = n_out;
+  return launch_mfma<EPI_NONE, MODE_NN>(g, st);
+}
+
+// dW[s] [rows_per_slot, n_out] = A[rows of s, :rows_per_slot]^T W[rows of s, :n_out]
+int32_t gemm_wgrad(const uint16_t* A, const uint16_t* W, uint16_t* C, int S, long long P, int rows_per_slot,
+                   int n_out, const int32_t* slot_offsets, const TileTable& t, hipStream_t st) {
+  MfmaArgs g{};
+  g.A = A;
+  g.W = W;
   g.C = C;
   g.P = (long long)S * rows_per_slot;
-  g.K = 0;
   g.w_rows = n_out;
   g.n_out = n_out;
   g.n_tiles = ceil_div(n_out, BN);
   g.which = 0;
   g.t = t;
-  g.kinfo = kinfo;
+  g.lda = rows_per_slot;
+  g.ldw = n_out;
+  g.slot_offsets = slot_offsets;
+  g.k_rows = P;
   g.rows_per_slot = rows_per_slot;
-  return launch_mfma<EPI_NONE, true>(g, st);
-}
-
-int32_t transpose_pad(const void* src, int C, const TrainWorkspace& w, uint16_t* dst, hipStream_t st) {
-  const dim3 grid((unsigned)(w.Kpad / 64), (unsigned)ceil_div(C, kTrCols));
-  hipLaunchKernelGGL(transpose_pad_kernel, grid, dim3(256), 0, st, (const uint16_t*)src, C, w.ktile, dst);
-  return lz::launch_status();
+  return launch_mfma<EPI_NONE, MODE_TN>(g, st);
 }
 
 }  // namespace
@@ -439,17 +348,6 @@ int32_t transpose_pad(const void* src, int C, const TrainWorkspace& w, uint16_t*
 extern "C" size_t lz_train_workspace_bytes(const lz_shape* shape) {
   if (!train_shape(shape)) return 0;
   return carve_train(nullptr, shape).total_bytes;
-}
-
-extern "C" int32_t lz_transpose_weights(const void* w, int32_t S, int32_t rows, int32_t cols, void* wt,
-                                        void* stream) {
-  if (S < 0 || rows < 1 || cols < 1 || rows % 64 != 0 || cols % 64 != 0) return LZ_ESHAPE;
-  if (S == 0) return LZ_OK;
-  if (!w || !wt || !aligned16(w) || !aligned16(wt)) return LZ_EINVAL;
-  if (S > 65535 || cols / 64 > 65535) return LZ_ESHAPE;
-  hipLaunchKernelGGL(transpose_weights_kernel, dim3(rows / 64, ceil_div(cols, kTrCols), S), dim3(256), 0, (hipStream_t)stream,
-                     (const uint16_t*)w, rows, cols, (uint16_t*)wt);
-  return lz::launch_status();
 }
 
 extern "C" int32_t lz_ffn_forward_train(const void* xp, const int32_t* slot_offsets, const void* w1, const void* w2,
@@ -510,7 +408,7 @@ extern "C" int32_t lz_route_backward(const float* dgates, const float* topk_gate
 }
 
 extern "C" int32_t lz_ffn_backward(const void* dyp, const void* xp, const void* z, const void* h,
-                                   const int32_t* slot_offsets, const void* w1t, const void* w2t,
+                                   const int32_t* slot_offsets, const void* w1, const void* w2,
                                    const lz_shape* shape, void* dxp, void* dw1, void* dw2, void* ws,
                                    size_t ws_bytes, void* stream) {
   TrainWorkspace w;
@@ -520,15 +418,15 @@ extern "C" int32_t lz_ffn_backward(const void* dyp, const void* xp, const void* 
   const int S = shape->N * shape->c;
   if (!dw1 || !dw2 || !slot_offsets) return LZ_EINVAL;
   if (!aligned16(dw1) || !aligned16(dw2)) return LZ_EINVAL;
-  if (P > 0 && (!dyp || !xp || !z || !h || !w1t || !w2t || !dxp)) return LZ_EINVAL;
-  if (P > 0 && (!aligned16(dyp) || !aligned16(xp) || !aligned16(z) || !aligned16(h) || !aligned16(dxp)))
+  if (P > 0 && (!dyp || !xp || !z || !h || !w1 || !w2 || !dxp)) return LZ_EINVAL;
+  if (P > 0 && (!aligned16(dyp) || !aligned16(xp) || !aligned16(z) || !aligned16(h) || !aligned16(dxp) ||
+                !aligned16(w1) || !aligned16(w2)))
     return LZ_EINVAL;
   hipStream_t st = (hipStream_t)stream;
   const int d = shape->d, ffn = shape->ffn, n1 = w.n1;
   const bool swiglu = shape->act == LZ_SWIGLU;
 
-  hipLaunchKernelGGL(wgrad_plan_kernel, dim3(1), dim3(256), 0, st, slot_offsets, S, P, d, n1, int(w.Kpad / 64), w.kinfo,
-                     w.ktile, w.virt_w2, w.virt_w1);
+  hipLaunchKernelGGL(virtual_rows_kernel, dim3(1), dim3(256), 0, st, S, d, n1, w.virt_w2, w.virt_w1);
   int32_t r = lz::launch_status();
   if (r != LZ_OK) return r;
   TileTable t_rows, t_w2, t_w1;
@@ -537,8 +435,8 @@ extern "C" int32_t lz_ffn_backward(const void* dyp, const void* xp, const void* 
   if ((r = build_table(w.virt_w1, S, (long long)S * n1, d / BN, 0, w.tiles_w1, st, &t_w1)) != LZ_OK) return r;
 
   if (P > 0) {
-    // dH = dyp W2
-    if ((r = gemm_rows((const uint16_t*)dyp, (const uint16_t*)w2t, w.dh, P, d, ffn, 0, t_rows, st)) != LZ_OK) return r;
+    // dH = dyp W2      (W2 [d, ffn]: contraction over its rows)
+    if ((r = gemm_dgrad((const uint16_t*)dyp, (const uint16_t*)w2, w.dh, P, d, ffn, 0, t_rows, st)) != LZ_OK) return r;
     // dZ = dH * act'(Z)
     const int ffn_vec = ffn / 8;
     const unsigned blocks = (unsigned)((P * ffn_vec + 255) / 256);
@@ -549,17 +447,14 @@ extern "C" int32_t lz_ffn_backward(const void* dyp, const void* xp, const void* 
       hipLaunchKernelGGL(act_backward_kernel<false>, dim3(blocks), dim3(256), 0, st, (const u32x4*)w.dh,
                          (const u32x4*)z, P, ffn_vec, (u32x4*)w.dz);
     if ((r = lz::launch_status()) != LZ_OK) return r;
-    // dxp = dZ W1
-    if ((r = gemm_rows(w.dz, (const uint16_t*)w1t, (uint16_t*)dxp, P, n1, d, 1, t_rows, st)) != LZ_OK) return r;
+    // dxp = dZ W1      (W1 [n1, d])
+    if ((r = gemm_dgrad(w.dz, (const uint16_t*)w1, (uint16_t*)dxp, P, n1, d, 1, t_rows, st)) != LZ_OK) return r;
   }
-  // dW2[s] = dyp_s^T H_s
-  if ((r = transpose_pad(dyp, d, w, w.ta, st)) != LZ_OK) return r;
-  if ((r = transpose_pad(h, ffn, w, w.tb, st)) != LZ_OK) return r;
-  if ((r = gemm_wgrad(w.ta, w.tb, (uint16_t*)dw2, S, d, ffn, w.kinfo, t_w2, st)) != LZ_OK) return r;
-  // dW1[s] = dZ_s^T xp_s
-  if ((r = transpose_pad(w.dz, n1, w, w.ta, st)) != LZ_OK) return r;
-  if ((r = transpose_pad(xp, d, w, w.tb, st)) != LZ_OK) return r;
-  return gemm_wgrad(w.ta, w.tb, (uint16_t*)dw1, S, n1, d, w.kinfo, t_w1, st);
+  // dW2[s] = dyp_s^T H_s,  dW1[s] = dZ_s^T xp_s
+  if ((r = gemm_wgrad((const uint16_t*)dyp, (const uint16_t*)h, (uint16_t*)dw2, S, P, d, ffn, slot_offsets, t_w2,
+                      st)) != LZ_OK)
+    return r;
+  return gemm_wgrad(w.dz, (const uint16_t*)xp, (uint16_t*)dw1, S, P, n1, d, slot_offsets, t_w1, st);
 }
 
 extern "C" int32_t lz_reduce_replica_grads(const void* dw_slot, const int32_t* slot_expert, int32_t S, int32_t E,

@@ -175,13 +175,46 @@ struct MfmaArgs {
   int n_tiles;          // column tiles per row tile
   int which;            // 0 = GEMM-1, 1 = GEMM-2: which unit lists and tickets of the tile table
   TileTable t;
-  // Ragged-K mode (VARK, the weight-gradient contractions): every slot owns rows_per_slot rows
-  // of C (row index = slot * rows_per_slot + m) and its own contraction length.  Slot s's
-  // operands are the blocks A_s [rows_per_slot, K_s] at A + rows_per_slot * kinfo[2s] and
-  // W_s [w_rows, K_s] at W + w_rows * kinfo[2s], with K_s = kinfo[2s+1] a multiple of 64.
-  const int32_t* kinfo;
+  // MODE_NN (data gradients): W is [S, K, ldw], the contraction runs over its rows.
+  // MODE_TN (weight gradients): both operands are K-major, A [k_rows, lda] and W [k_rows, ldw];
+  // slot s contracts over their rows [slot_offsets[s], slot_offsets[s+1]) and owns rows_per_slot
+  // rows of C (row index = s * rows_per_slot + m, m = column of A).
+  int lda, ldw;
+  const int32_t* slot_offsets;
+  long long k_rows;
   int rows_per_slot;
 };
+
+// Operand layouts of the contraction C[m, n] = sum_k A(m, k) W(n, k):
+//   MODE_NT  A [m, k], W [n, k]: both contiguous along k (the forward)
+//   MODE_NN  A [m, k], W [k, n]
+//   MODE_TN  A [k, m], W [k, n], a different k range for every slot
+// A k-major operand tile lies in LDS as 64 k-rows of 256 columns (512 B each) and is read with
+// ds_read_b64_tr_b16, which hands every lane four k-values of one column: the 16 lanes of a
+// group supply the addresses of 4 k-rows x 4 column quads, and lane i receives column i of the
+// group's 16 at those four k.  Two such reads give the lane the same 8 consecutive k of its
+// column that a ds_read_b128 gives it from a k-contiguous tile, so the MFMAs and the epilogue
+// do not change.
+enum { MODE_NT = 0, MODE_NN = 1, MODE_TN = 2 };
+typedef short i16x4 __attribute__((ext_vector_type(4)));
+typedef int i32x4 __attribute__((ext_vector_type(4)));
+
+// The four words of a raw buffer descriptor (base, stride 0, bytes, data format word).
+__device__ __forceinline__ i32x4 rsrc_words(const void* base, uint32_t bytes) {
+  const uint64_t b = (uint64_t)base;
+  return i32x4{(int)(uint32_t)b, (int)(uint32_t)((b >> 32) & 0xFFFFu), (int)bytes, 0x00020000};
+}
+
+// 16 bytes per lane from a buffer straight into LDS at lds_base + 16 * lane, written as assembly:
+// in the k-major modes the compiler must not know that loads into LDS are in flight, or it
+// makes every transposing LDS read wait for all of them (it cannot tell that the two never
+// touch the same bytes).  The kernel orders loads and reads itself (s_waitcnt vmcnt + barrier).
+__device__ __forceinline__ void load16_to_lds(i32x4 rsrc, uint32_t lds_base, int voffset, int soffset) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+               :
+               : "s"(lds_base), "v"(voffset), "s"(rsrc), "s"(soffset)
+               : "memory");  // m0 is scratch to the compiler as well: it loads it right before each use
+}
 
 // Activations on the fp32 accumulators of the bf16 path.  The result is rounded to bf16
 // (relative step 2^-9), so hardware exp2 / rcp (1 ulp) are used; erf is the
@@ -232,10 +265,11 @@ __device__ __forceinline__ void sched_slice() {
 // One output tile of 64*XF rows x 256 weight rows.  XF = 32-row activation fragments per
 // wave: the 2x2 waves each own (32*XF) x 128 of the tile, so a slot's ragged last tile costs
 // MFMAs and activation loads only for its rows rounded up to 64.
-template <int EPI, int XF, bool VARK>
+template <int EPI, int XF, int MODE>
 __device__ __forceinline__ void gemm_tile(const MfmaArgs& a, char* smem, int slot, int row0, int row_end, int n0) {
+  constexpr bool TA = MODE == MODE_TN, TB = MODE != MODE_NT;  // k-major left / right operand
   constexpr int KS = BK / 16;             // 16-wide MFMA slices per stage
-  constexpr int kLoadsX = 2 * XF;         // 1-KiB wave loads per wave for the activation tile (8 rows each)
+  constexpr int kLoadsX = TA ? 8 : 2 * XF;  // 1-KiB wave loads per wave for the left tile (8 rows, or 2 k-rows, each)
   constexpr int kLoadsW = 8;              // ... for the 256-row weight tile
   // The empty asm keeps the per-lane address arithmetic below inside the tile: hoisted out of
   // the caller's tile loop it would be carried in registers through the whole kernel and spill.
@@ -250,51 +284,83 @@ __device__ __forceinline__ void gemm_tile(const MfmaArgs& a, char* smem, int slo
   int K = a.K;
   const uint16_t* tileA;
   const uint16_t* tileW;
-  uint32_t w_extent;  // bytes of the weight block the descriptor covers
-  if constexpr (VARK) {
-    // the weight descriptor starts at this tile's first weight row: 256 rows of K_s stay far
-    // below 2^31 bytes whatever the slot's length
-    const long long col0 = a.kinfo[2 * slot];
-    K = a.kinfo[2 * slot + 1];
-    tileA = a.A + (size_t)a.rows_per_slot * col0 + (size_t)(row0 - slot * a.rows_per_slot) * K;
-    tileW = a.W + (size_t)a.w_rows * col0 + (size_t)n0 * K;
-    const int w_left = a.w_rows - n0 < BN ? a.w_rows - n0 : BN;
-    w_extent = (uint32_t)w_left * (uint32_t)K * 2u;
+  uint32_t a_extent, w_extent;          // bytes the two descriptors cover
+  int stepA = BK * 2, stepW = BK * 2;   // bytes one K step advances in each operand
+  if constexpr (MODE == MODE_TN) {
+    // The descriptors start at the slot's first row and this tile's first column and end with
+    // the slot's last row: the rows of the last, partial K step that belong to the next slot
+    // read as zero.
+    long long s0, s1;
+    clip_slot(a.slot_offsets, slot, a.k_rows, &s0, &s1);
+    K = int(s1 - s0);
+    const int m0 = row0 - slot * a.rows_per_slot;
+    tileA = a.A + (size_t)s0 * a.lda + m0;
+    tileW = a.W + (size_t)s0 * a.ldw + n0;
+    a_extent = K > 0 ? ((uint32_t)K * (uint32_t)a.lda - (uint32_t)m0) * 2u : 0u;
+    w_extent = K > 0 ? ((uint32_t)K * (uint32_t)a.ldw - (uint32_t)n0) * 2u : 0u;
+    stepA = 64 * a.lda * 2;
+    stepW = 64 * a.ldw * 2;
+  } else if constexpr (MODE == MODE_NN) {
+    tileA = a.A + (size_t)row0 * K;
+    a_extent = (uint32_t)n_rows * (uint32_t)K * 2u;
+    tileW = a.W + (size_t)slot * K * a.ldw;
+    w_extent = (uint32_t)K * (uint32_t)a.ldw * 2u;
+    stepW = 64 * a.ldw * 2;
   } else {
     tileA = a.A + (size_t)row0 * K;
+    a_extent = (uint32_t)n_rows * (uint32_t)K * 2u;
     tileW = a.W + (size_t)slot * a.w_rows * K;
     w_extent = (uint32_t)((unsigned long long)a.w_rows * K * 2);
   }
-  const __amdgpu_buffer_rsrc_t rsrcA = __builtin_amdgcn_make_buffer_rsrc(
-      (void*)tileA, 0, (int)((uint32_t)n_rows * (uint32_t)K * 2u), 0x00020000);
+  const __amdgpu_buffer_rsrc_t rsrcA = __builtin_amdgcn_make_buffer_rsrc((void*)tileA, 0, (int)a_extent, 0x00020000);
   const __amdgpu_buffer_rsrc_t rsrcB = __builtin_amdgcn_make_buffer_rsrc((void*)tileW, 0, (int)w_extent, 0x00020000);
   const __amdgpu_buffer_rsrc_t rsrcNull = __builtin_amdgcn_make_buffer_rsrc((void*)a.A, 0, 0, 0x00020000);
+  const i32x4 wordsA = rsrc_words(tileA, a_extent), wordsB = rsrc_words(tileW, w_extent);
+  const i32x4 wordsNull = rsrc_words(a.A, 0);
+  const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)smem;
 
   // ---- per-lane global offsets of the direct-to-LDS loads of one stage.
   // Load u of an operand tile fills LDS bytes [u*1024, u*1024+1024): 8 whole rows, lane l
   // landing at row 8u + l/8, 16-byte chunk l%8.  That LDS chunk must hold logical chunk
   // (l%8) ^ swz(row), so the lane fetches that one (the swizzle is applied on the global side
   // because a direct-to-LDS load fixes the LDS side to lane order).
+  //
+  // k-major operand: load u fills two k-rows of 512 B, lane l landing at k-row 2u + l/32, 16-byte
+  // piece l%32, which must hold logical piece (l%32) ^ 4*(k-row % 4): the four k-rows that one
+  // transposing read touches at the same columns then lie in four different quarters of the banks.
+  auto voff_kmajor = [&](int i, int ld, int col0) {
+    const int kr = (wave * 8 + i) * 2 + (lane >> 5);
+    const int piece = (lane & 31) ^ ((kr & 3) << 2);
+    return (int)(((uint32_t)kr * (uint32_t)ld + (uint32_t)col0 + (uint32_t)piece * 8u) * 2u);
+  };
   int voffX[kLoadsX], voffW[kLoadsW];
 #pragma unroll
   for (int i = 0; i < kLoadsX; ++i) {
-    const int r = (wave * kLoadsX + i) * 8 + (lane >> 3);
-    const int chunk = (lane & 7) ^ swz(r);
-    const int ga = r < n_rows ? r : n_rows - 1;  // rows past the tile's end repeat its last row (never stored)
-    voffX[i] = (int)(((uint32_t)ga * (uint32_t)K + (uint32_t)chunk * 8u) * 2u);
+    if constexpr (TA) {
+      voffX[i] = voff_kmajor(i, a.lda, 0);  // columns past the operand's edge fetch its neighbours: never stored
+    } else {
+      const int r = (wave * kLoadsX + i) * 8 + (lane >> 3);
+      const int chunk = (lane & 7) ^ swz(r);
+      const int ga = r < n_rows ? r : n_rows - 1;  // rows past the tile's end repeat its last row (never stored)
+      voffX[i] = (int)(((uint32_t)ga * (uint32_t)K + (uint32_t)chunk * 8u) * 2u);
+    }
   }
 #pragma unroll
   for (int i = 0; i < kLoadsW; ++i) {
-    const int r = (wave * kLoadsW + i) * 8 + (lane >> 3);
-    const int chunk = (lane & 7) ^ swz(r);
-    int gb;
-    if (EPI == EPI_SWIGLU) {
-      const int f = r >> 5;  // fragment index: even = gate rows, odd = up rows
-      gb = n0 + (f >> 1) * 32 + (r & 31) + ((f & 1) ? a.up_row0 : 0);
+    if constexpr (TB) {
+      voffW[i] = voff_kmajor(i, a.ldw, MODE == MODE_NN ? n0 : 0);
     } else {
-      gb = VARK ? r : n0 + r;
+      const int r = (wave * kLoadsW + i) * 8 + (lane >> 3);
+      const int chunk = (lane & 7) ^ swz(r);
+      int gb;
+      if (EPI == EPI_SWIGLU) {
+        const int f = r >> 5;  // fragment index: even = gate rows, odd = up rows
+        gb = n0 + (f >> 1) * 32 + (r & 31) + ((f & 1) ? a.up_row0 : 0);
+      } else {
+        gb = n0 + r;
+      }
+      voffW[i] = (int)(((uint32_t)gb * (uint32_t)K + (uint32_t)chunk * 8u) * 2u);
     }
-    voffW[i] = (int)(((uint32_t)gb * (uint32_t)K + (uint32_t)chunk * 8u) * 2u);
   }
 
   // ---- fragment read addresses: lane l reads row (l%32) of a 32-row fragment, logical chunk
@@ -307,6 +373,30 @@ __device__ __forceinline__ void gemm_tile(const MfmaArgs& a, char* smem, int slo
   }
   const int xbase = wm * 32 * XF * kRowBytes;               // this wave's activation rows
   const int wbase = BM * kRowBytes + wn * 128 * kRowBytes;  // this wave's 128 weight rows
+  // k-major tiles: lane 16g + s supplies the address of k-row 8*(g/2) + s/4 (of the 16-wide
+  // slice), column quad s%4 of the group's 16 columns (16*(g%2) into the 32-column fragment)
+  int tfoX[XF], tfoW[4];
+  {
+    const int g = lane >> 4, s = lane & 15;
+    const int part = (8 * (g >> 1) + (s >> 2)) * 512 + ((2 * (g & 1) + ((s >> 1) & 1)) << 4) + ((s & 1) << 3);
+#pragma unroll
+    for (int j = 0; j < XF; ++j) tfoX[j] = part + 64 * ((XF * wm + j) ^ (s >> 2));
+#pragma unroll
+    for (int i = 0; i < 4; ++i) tfoW[i] = BM * kRowBytes + part + 64 * ((4 * wn + i) ^ (s >> 2));
+  }
+  auto read_kmajor = [&](const char* p) {
+    const i16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) i16x4*)p);
+    const i16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) i16x4*)(p + 4 * 512));
+    return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+  };
+  auto frag_x = [&](const char* stage, int ks, int j) {
+    if constexpr (TA) return read_kmajor(stage + ks * 16 * 512 + tfoX[j]);
+    else return *(const bf16x8*)(stage + xbase + j * 32 * kRowBytes + fragoff[ks]);
+  };
+  auto frag_w = [&](const char* stage, int ks, int i) {
+    if constexpr (TB) return read_kmajor(stage + ks * 16 * 512 + tfoW[i]);
+    else return *(const bf16x8*)(stage + wbase + i * 32 * kRowBytes + fragoff[ks]);
+  };
 
   f32x16 acc[4][XF];
 #pragma unroll
@@ -330,7 +420,7 @@ __device__ __forceinline__ void gemm_tile(const MfmaArgs& a, char* smem, int slo
   // activation loads go first.  (Measured on three workloads: 6 + rest + 0 beats 8 + half + half
   // by 2-11 %, and 4, 5, 7, 8, 10, 12 or all 16 after the barrier; activations first is 0.7 %
   // ahead of weights first on the first GEMM and level on the second.)
-  const int k_steps = K / BK;
+  const int k_steps = (K + BK - 1) / BK;
   constexpr int kLoads = kLoadsW + kLoadsX;
   auto issue = [&](int stage, int step, int q0, int q1) {
     // a step past the end of K is "loaded" through a zero-length descriptor: no memory traffic
@@ -339,35 +429,46 @@ __device__ __forceinline__ void gemm_tile(const MfmaArgs& a, char* smem, int slo
     const __amdgpu_buffer_rsrc_t rb = real ? rsrcB : rsrcNull;
     char* sX = smem + stage * kStageBytes;
     char* sW = sX + BM * kRowBytes;
+    if constexpr (MODE != MODE_NT) {
+      const i32x4 wa = real ? wordsA : wordsNull, wb = real ? wordsB : wordsNull;
+      const uint32_t ldsX = lds0 + stage * kStageBytes, ldsW = ldsX + BM * kRowBytes;
+#pragma unroll
+      for (int q = q0; q < q1; ++q) {
+        if (q < kLoadsX) load16_to_lds(wa, ldsX + (wave * kLoadsX + q) * 1024, voffX[q], step * stepA);
+        else load16_to_lds(wb, ldsW + (wave * kLoadsW + q - kLoadsX) * 1024, voffW[q - kLoadsX], step * stepW);
+      }
+      return;
+    }
 #pragma unroll
     for (int q = q0; q < q1; ++q) {
       if (q < kLoadsX) {
         const int u = wave * kLoadsX + q;
         __builtin_amdgcn_raw_ptr_buffer_load_lds(ra, (__attribute__((address_space(3))) void*)(sX + u * 1024), 16,
-                                                 voffX[q], step * BK * 2, 0, 0);
+                                                 voffX[q], step * stepA, 0, 0);
       } else {
         const int u = wave * kLoadsW + (q - kLoadsX);
         __builtin_amdgcn_raw_ptr_buffer_load_lds(rb, (__attribute__((address_space(3))) void*)(sW + u * 1024), 16,
-                                                 voffW[q - kLoadsX], step * BK * 2, 0, 0);
+                                                 voffW[q - kLoadsX], step * stepW, 0, 0);
       }
     }
   };
+  constexpr int kDsReads = (TB ? 8 : 4) + (TA ? 2 * XF : XF);  // LDS read instructions per slice
   constexpr int kAfterBarrier = 6;                 // loads issued in the slice after the barrier,
   constexpr int kSlice0 = kLoads - kAfterBarrier;  // and in slice 0 of the next step
   bf16x8 xf[2][XF], wf[2][4];
   // read order = order of first use by the MFMAs (weight fragment 0, all activation fragments,
   // weight fragments 1..3)
   auto read_frags = [&](const char* stage, int ks, int set) {
-    wf[set][0] = *(const bf16x8*)(stage + wbase + fragoff[ks]);
+    wf[set][0] = frag_w(stage, ks, 0);
 #pragma unroll
-    for (int j = 0; j < XF; ++j) xf[set][j] = *(const bf16x8*)(stage + xbase + j * 32 * kRowBytes + fragoff[ks]);
+    for (int j = 0; j < XF; ++j) xf[set][j] = frag_x(stage, ks, j);
 #pragma unroll
-    for (int i = 1; i < 4; ++i) wf[set][i] = *(const bf16x8*)(stage + wbase + i * 32 * kRowBytes + fragoff[ks]);
+    for (int i = 1; i < 4; ++i) wf[set][i] = frag_w(stage, ks, i);
   };
   auto read_one = [&](const char* stage, int ks, int set, int r) {  // r-th fragment in that order
-    if (r == 0) wf[set][0] = *(const bf16x8*)(stage + wbase + fragoff[ks]);
-    else if (r <= XF) xf[set][r - 1] = *(const bf16x8*)(stage + xbase + (r - 1) * 32 * kRowBytes + fragoff[ks]);
-    else wf[set][r - XF] = *(const bf16x8*)(stage + wbase + (r - XF) * 32 * kRowBytes + fragoff[ks]);
+    if (r == 0) wf[set][0] = frag_w(stage, ks, 0);
+    else if (r <= XF) xf[set][r - 1] = frag_x(stage, ks, r - 1);
+    else wf[set][r - XF] = frag_w(stage, ks, r - XF);
   };
   // Fragment reads and direct-to-LDS loads of one slice, alternating in program order.  The
   // compiler cannot tell that a load's LDS destination and a fragment read never overlap, so it
@@ -404,18 +505,18 @@ __device__ __forceinline__ void gemm_tile(const MfmaArgs& a, char* smem, int slo
     const char* nx = smem + (cur ^ 1) * kStageBytes;
     reads_and_loads(st, 1, 1, cur ^ 1, kt + 1, kAfterBarrier, kLoads);
     mma(0);
-    sched_slice<0, 4 + XF, 4 * XF, kSlice0>();
+    sched_slice<0, kDsReads, 4 * XF, kSlice0>();
     read_frags(st, 2, 0);
     mma(1);
-    sched_slice<0, 4 + XF, 4 * XF, 0>();
+    sched_slice<0, kDsReads, 4 * XF, 0>();
     read_frags(st, 3, 1);
     mma(0);
-    sched_slice<0, 4 + XF, 4 * XF, 0>();
+    sched_slice<0, kDsReads, 4 * XF, 0>();
     __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wave's loads of the next stage are in LDS
     __syncthreads();                     // everyone's are; nobody reads stage `cur` any more
     reads_and_loads(nx, 0, 0, cur, kt + 2, 0, kAfterBarrier);
     mma(1);
-    sched_slice<0, 4 + XF, 4 * XF, kAfterBarrier>();
+    sched_slice<0, kDsReads, 4 * XF, kAfterBarrier>();
   }
   __builtin_amdgcn_s_waitcnt(0x0F70);  // drain the (empty) trailing loads before LDS is reused
 
@@ -493,7 +594,7 @@ __device__ __forceinline__ void gemm_tile(const MfmaArgs& a, char* smem, int slo
 // its own pace.  (The hardware hands the workgroups of an ordinary launch to the XCDs strictly
 // in order of their index: there an XCD whose tiles take longer holds back the workgroups
 // queued behind it for every other XCD, which costs 10-40 % on ragged plans.)
-template <int EPI, bool VARK = false>
+template <int EPI, int MODE = MODE_NT>
 __global__ __launch_bounds__(256, 1) void gemm_mfma_kernel(MfmaArgs a) {
 #if defined(__HIP_DEVICE_COMPILE__)  // the host pass only needs the launch stub, not the gfx950 builtins
   extern __shared__ __attribute__((aligned(1024))) char smem[];
@@ -525,10 +626,10 @@ __global__ __launch_bounds__(256, 1) void gemm_mfma_kernel(MfmaArgs a) {
       const int row_end = a.t.row_end[row_tile];
       const int n0 = nt * BN_OUT;
       const int rows = row_end - row0;  // > 0; more than 256 means a full tile
-      if (rows > 192) gemm_tile<EPI, 4, VARK>(a, smem, slot, row0, row_end, n0);
-      else if (rows > 128) gemm_tile<EPI, 3, VARK>(a, smem, slot, row0, row_end, n0);
-      else if (rows > 64) gemm_tile<EPI, 2, VARK>(a, smem, slot, row0, row_end, n0);
-      else gemm_tile<EPI, 1, VARK>(a, smem, slot, row0, row_end, n0);
+      if (rows > 192) gemm_tile<EPI, 4, MODE>(a, smem, slot, row0, row_end, n0);
+      else if (rows > 128) gemm_tile<EPI, 3, MODE>(a, smem, slot, row0, row_end, n0);
+      else if (rows > 64) gemm_tile<EPI, 2, MODE>(a, smem, slot, row0, row_end, n0);
+      else gemm_tile<EPI, 1, MODE>(a, smem, slot, row0, row_end, n0);
     }
   }
   // the last workgroup to finish leaves the tickets at zero for the next launch on this table
@@ -542,9 +643,9 @@ __global__ __launch_bounds__(256, 1) void gemm_mfma_kernel(MfmaArgs a) {
 #endif
 }
 
-template <int EPI, bool VARK = false>
+template <int EPI, int MODE = MODE_NT>
 int32_t launch_mfma(const MfmaArgs& a, hipStream_t st) {
-  void (*kern)(MfmaArgs) = gemm_mfma_kernel<EPI, VARK>;
+  void (*kern)(MfmaArgs) = gemm_mfma_kernel<EPI, MODE>;
   static bool configured = false;  // per-process attribute; idempotent, so a benign race at worst
   static int n_workgroups = 0;
   if (!configured) {

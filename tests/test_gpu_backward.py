@@ -35,12 +35,6 @@ def _ffn_backward_case(cfg, counts, seed):
     shape = lz.Shape.from_config(cfg)
     bf = torch.bfloat16
     w1, w2 = to_dev(w["w1"][slot_expert], True), to_dev(w["w2"][slot_expert], True)
-    w1t = torch.empty((S, cfg.d, n1), dtype=bf, device=DEV)
-    w2t = torch.empty((S, cfg.ffn, cfg.d), dtype=bf, device=DEV)
-    lz.lz_transpose_weights(w1, S, n1, cfg.d, w1t)
-    lz.lz_transpose_weights(w2, S, cfg.d, cfg.ffn, w2t)
-    assert torch.equal(w1t.view(torch.int16), w1.transpose(1, 2).contiguous().view(torch.int16))
-    assert torch.equal(w2t.view(torch.int16), w2.transpose(1, 2).contiguous().view(torch.int16))
     nbytes = lz.lz_train_workspace_bytes(shape)
     assert nbytes > 0
     ws = torch.empty(nbytes, dtype=torch.uint8, device=DEV)
@@ -52,7 +46,7 @@ def _ffn_backward_case(cfg, counts, seed):
     dxp = torch.zeros((P, cfg.d), dtype=bf, device=DEV)
     dw1 = torch.full((S, n1, cfg.d), 7.0, dtype=bf, device=DEV)
     dw2 = torch.full((S, cfg.d, cfg.ffn), 7.0, dtype=bf, device=DEV)
-    lz.lz_ffn_backward(dyp, xp, z, h, off, w1t, w2t, shape, dxp, dw1, dw2, ws, nbytes)
+    lz.lz_ffn_backward(dyp, xp, z, h, off, w1, w2, shape, dxp, dw1, dw2, ws, nbytes)
     torch.cuda.synchronize()
 
     # forward intermediates
@@ -83,8 +77,8 @@ def _ffn_backward_case(cfg, counts, seed):
                                        ("swiglu", 512, 384)])
 def test_ffn_forward_train_and_backward_ragged(act, d, ffn):
     cfg = scaled(CONFIGS["c1_tiny"], act=act, dtype="bf16", T=700, k=2, d=d, ffn=ffn, N=4, c=2)
-    # several row tiles, a tile boundary + 1, an empty slot, one-row slots, ragged tails; K of the
-    # weight gradients: 320, 128 (empty), 128 (one row), 512, 320, 256, 128, 128
+    # several row tiles, a tile boundary + 1, an empty slot, one-row slots, ragged tails: the weight
+    # gradients contract over 257, 0, 1, 512, 300, 255, 74 and 1 rows (whole and partial K steps)
     _ffn_backward_case(cfg, [257, 0, 1, 512, 300, 255, 74, 1], 3)
 
 
