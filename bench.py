@@ -101,8 +101,8 @@ def replan_latency(torch, lz, dev):
         re = lz.lz_replan(old_plan, cfg.base_N, cfg.base_c, alive, t_e, cfg.c, cfg.f)
         host.append((time.perf_counter() - t0) * 1e3)
     n1 = w["w1"].shape[1]
-    w1n = torch.empty((shape_new.S, n1, cfg.d), dtype=torch.bfloat16, device=dev)
-    w2n = torch.empty((shape_new.S, cfg.d, cfg.ffn), dtype=torch.bfloat16, device=dev)
+    w1n = torch.empty((shape_new.S, cfg.d, n1), dtype=torch.bfloat16, device=dev)
+    w2n = torch.empty((shape_new.S, cfg.ffn, cfg.d), dtype=torch.bfloat16, device=dev)
     a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     copy = []
     for _ in range(5):
@@ -132,7 +132,7 @@ def training_pass(torch, lz, layer, cfg, logits, x, iters=5):
         return None
     layer.enable_training()
     dy = torch.randn((s.T, s.d), device=layer.device).to(torch.bfloat16)
-    n1 = layer.w1.shape[1]
+    n1 = layer.w1.shape[2]
     P, S = s.P, s.S
 
     def reduce():

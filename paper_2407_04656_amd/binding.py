@@ -329,7 +329,7 @@ class MoELayer:
     """Owns the device buffers of one layer shape and runs the five calls in order.
 
     Buffer management only: torch allocates, the library computes.  Weights are per-slot
-    copies laid out as w1[S, n1, d], w2[S, d, ffn] (see include/lazarus_moe.h).
+    copies laid out input-major, w1[S, d, n1], w2[S, ffn, d] (see include/lazarus_moe.h).
     """
 
     def __init__(self, shape: Shape, device="cuda:0"):
@@ -370,7 +370,9 @@ class MoELayer:
         self.w1, self.w2 = w1, w2
 
     def load_expert_weights(self, w1_experts, w2_experts, slot_expert):
-        """Give every slot its own copy of its expert's weights (host arrays indexed by expert)."""
+        """Give every slot its own copy of its expert's weights.  The host arrays are indexed by
+        expert and come in the usual [out, in] layout (w1 [E, n1, d], w2 [E, d, ffn]); the device
+        copies are their transposes."""
         import torch
         s = self.shape
         tdt = torch.float32 if s.dtype == LZ_F32 else torch.bfloat16
@@ -379,11 +381,11 @@ class MoELayer:
             t = torch.from_numpy(a)
             if s.dtype == LZ_BF16:
                 t = t.view(torch.bfloat16)
-            return t.to(self.device)
+            return t.to(self.device).t().contiguous()
 
         n1 = w1_experts.shape[1]
-        self.w1 = torch.empty((s.S, n1, s.d), dtype=tdt, device=self.device)
-        self.w2 = torch.empty((s.S, s.d, s.ffn), dtype=tdt, device=self.device)
+        self.w1 = torch.empty((s.S, s.d, n1), dtype=tdt, device=self.device)
+        self.w2 = torch.empty((s.S, s.ffn, s.d), dtype=tdt, device=self.device)
         cache = {}
         for slot, e in enumerate(np.asarray(slot_expert)):
             e = int(e)
@@ -426,7 +428,7 @@ class MoELayer:
         import torch
         s, dev = self.shape, self.device
         bf = torch.bfloat16
-        n1 = self.w1.shape[1]
+        n1 = self.w1.shape[2]
         self.train_ws_bytes = lz_train_workspace_bytes(s)
         if self.train_ws_bytes == 0:
             raise LzError(LZ_ESHAPE, "lz_train_workspace_bytes")
@@ -438,10 +440,10 @@ class MoELayer:
         self.dx = torch.empty((s.T, s.d), dtype=bf, device=dev)
         self.dgates = torch.empty((s.T, s.k), dtype=torch.float32, device=dev)
         self.dlogits = torch.empty((s.T, s.E), dtype=torch.float32, device=dev)
-        self.dw1_slot = torch.empty((s.S, n1, s.d), dtype=bf, device=dev)
-        self.dw2_slot = torch.empty((s.S, s.d, s.ffn), dtype=bf, device=dev)
-        self.dw1 = torch.empty((s.E, n1, s.d), dtype=bf, device=dev)
-        self.dw2 = torch.empty((s.E, s.d, s.ffn), dtype=bf, device=dev)
+        self.dw1_slot = torch.empty((s.S, s.d, n1), dtype=bf, device=dev)
+        self.dw2_slot = torch.empty((s.S, s.ffn, s.d), dtype=bf, device=dev)
+        self.dw1 = torch.empty((s.E, s.d, n1), dtype=bf, device=dev)
+        self.dw2 = torch.empty((s.E, s.ffn, s.d), dtype=bf, device=dev)
 
     def forward_train(self, logits, x):
         self.route(logits)

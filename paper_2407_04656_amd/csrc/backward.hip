@@ -3,20 +3,22 @@
 // replicas, Sec. 5, but prints no backward formulas).
 //
 //   combine      dgates[t,kk] = <dy[t], yp[row]>,  dyp[row] = gates[t,kk] dy[t]      HBM streaming
-//   GEMM-2       dH = dyp W2            (dgrad)    dW2[s] = dyp_s^T H_s   (wgrad)     MFMA
+//   GEMM-2       dH = dyp W2^T          (dgrad)    dW2[s] = H_s^T dyp_s   (wgrad)     MFMA   W2[s] = [ffn, d]
 //   activation   dZ = dH * act'(Z)                                                  HBM streaming
-//   GEMM-1       dxp = dZ W1            (dgrad)    dW1[s] = dZ_s^T xp_s   (wgrad)     MFMA
+//   GEMM-1       dxp = dZ W1^T          (dgrad)    dW1[s] = xp_s^T dZ_s   (wgrad)     MFMA   W1[s] = [d, n1]
 //   permute      dx[t] = sum_kk dxp[row(t,kk)]                                      HBM streaming
 //   gate         dlogits = softmax backward on the k selected logits
 //   replicas     dW[e] = sum over the slots that hold e                             HBM streaming
 //
-// Every contraction runs on the forward's grouped MFMA kernel.  The data gradients contract
-// over a weight matrix's rows and the weight gradients over a slot's rows (a different length
-// for every slot), so one or both operands arrive with the contraction index as their slow
-// dimension: the kernel's k-major modes stream such tiles into LDS as they are and transpose
-// them on the way to the registers (gfx950's transposing LDS reads), so no transposed copy of
-// weights or activations is ever written.  The weight gradients run over S x (rows of the
-// weight matrix) virtual rows; each tile takes its contraction range from slot_offsets.
+// Every contraction runs on the forward's grouped MFMA kernel in one of its three operand
+// modes.  The weights are stored input-major ([d, n1] and [ffn, d]: the forward contracts over
+// their rows), so the data gradients contract along their rows' direction (both operands
+// k-contiguous) and the weight gradients over a slot's rows of two activation matrices (both
+// operands k-major, a different length for every slot).  k-major tiles stream into LDS as they
+// lie in memory and are transposed on the way to the registers (gfx950's transposing LDS
+// reads): no transposed copy of weights or activations is ever written.  The weight gradients
+// run over S x (rows of the weight matrix) virtual rows; each tile takes its contraction range
+// from slot_offsets.
 #include "gemm_mfma.h"
 
 namespace {
@@ -231,8 +233,8 @@ struct TrainWorkspace {
   int32_t* virt_w1;    // [S+1]
   void* tiles_fwd;     // rows of the batch: lists for n1 / 256 and d / 256 column tiles
   void* tiles_bwd;     // rows of the batch: lists for ffn / 256 and d / 256 column tiles
-  void* tiles_w2;      // S * d virtual rows, ffn / 256 column tiles
-  void* tiles_w1;      // S * n1 virtual rows, d / 256 column tiles
+  void* tiles_w2;      // S * ffn virtual rows, d / 256 column tiles
+  void* tiles_w1;      // S * d virtual rows, n1 / 256 column tiles
   size_t total_bytes;
   int n1;
 };
@@ -256,8 +258,8 @@ TrainWorkspace carve_train(void* ws, const lz_shape* s) {
   w.virt_w1 = (int32_t*)take(sizeof(int32_t) * (S + 1));
   w.tiles_fwd = take(tile_table_bytes(P, S, BM, kGroupM, ceil_div(w.n1, BN), s->d / BN));
   w.tiles_bwd = take(tile_table_bytes(P, S, BM, kGroupM, ceil_div(s->ffn, BN), s->d / BN));
-  w.tiles_w2 = take(tile_table_bytes((long long)S * s->d, S, BM, kGroupM, ceil_div(s->ffn, BN), 0));
-  w.tiles_w1 = take(tile_table_bytes((long long)S * w.n1, S, BM, kGroupM, s->d / BN, 0));
+  w.tiles_w2 = take(tile_table_bytes((long long)S * s->ffn, S, BM, kGroupM, s->d / BN, 0));
+  w.tiles_w1 = take(tile_table_bytes((long long)S * s->d, S, BM, kGroupM, ceil_div(w.n1, BN), 0));
   w.total_bytes = size_t(p - (char*)ws);
   return w;
 }
@@ -288,7 +290,7 @@ int32_t build_table(const int32_t* offsets, int S, long long rows, int n_a, int 
 }
 
 // C[rows, n_out] = A[rows, K] W[slot][n_out, K]^T over the batch's ragged row ranges
-int32_t gemm_rows(const uint16_t* A, const uint16_t* W, uint16_t* C, long long P, int K, int n_out, int which,
+int32_t gemm_nt(const uint16_t* A, const uint16_t* W, uint16_t* C, long long P, int K, int n_out, int which,
                   const TileTable& t, hipStream_t st) {
   MfmaArgs g{};
   g.A = A;
@@ -305,7 +307,7 @@ int32_t gemm_rows(const uint16_t* A, const uint16_t* W, uint16_t* C, long long P
 }
 
 // C[rows, n_out] = A[rows, K] W[slot][K, n_out] over the batch's ragged row ranges
-int32_t gemm_dgrad(const uint16_t* A, const uint16_t* W, uint16_t* C, long long P, int K, int n_out, int which,
+int32_t gemm_nn(const uint16_t* A, const uint16_t* W, uint16_t* C, long long P, int K, int n_out, int which,
                    const TileTable& t, hipStream_t st) {
   MfmaArgs g{};
   g.A = A;
@@ -359,13 +361,14 @@ extern "C" int32_t lz_ffn_forward_train(const void* xp, const int32_t* slot_offs
   const long long P = (long long)shape->T * shape->k;
   if (P == 0) return LZ_OK;
   if (!xp || !slot_offsets || !w1 || !w2 || !z || !h || !yp) return LZ_EINVAL;
-  if (!aligned16(z) || !aligned16(h) || !aligned16(yp)) return LZ_EINVAL;
+  if (!aligned16(z) || !aligned16(h) || !aligned16(yp) || !aligned16(xp) || !aligned16(w1) || !aligned16(w2))
+    return LZ_EINVAL;
   hipStream_t st = (hipStream_t)stream;
   const int S = shape->N * shape->c;
   TileTable t;
   int32_t r = build_table(slot_offsets, S, P, ceil_div(w.n1, BN), shape->d / BN, w.tiles_fwd, st, &t);
   if (r != LZ_OK) return r;
-  r = gemm_rows((const uint16_t*)xp, (const uint16_t*)w1, (uint16_t*)z, P, shape->d, w.n1, 0, t, st);
+  r = gemm_nn((const uint16_t*)xp, (const uint16_t*)w1, (uint16_t*)z, P, shape->d, w.n1, 0, t, st);
   if (r != LZ_OK) return r;
   const int ffn_vec = shape->ffn / 8;
   const unsigned blocks = (unsigned)((P * ffn_vec + 255) / 256);
@@ -377,7 +380,7 @@ extern "C" int32_t lz_ffn_forward_train(const void* xp, const int32_t* slot_offs
                        (u32x4*)h);
   r = lz::launch_status();
   if (r != LZ_OK) return r;
-  return gemm_rows((const uint16_t*)h, (const uint16_t*)w2, (uint16_t*)yp, P, shape->ffn, shape->d, 1, t, st);
+  return gemm_nn((const uint16_t*)h, (const uint16_t*)w2, (uint16_t*)yp, P, shape->ffn, shape->d, 1, t, st);
 }
 
 extern "C" int32_t lz_combine_backward(const void* dy, const void* yp, const int32_t* pair_to_row,
@@ -426,17 +429,17 @@ extern "C" int32_t lz_ffn_backward(const void* dyp, const void* xp, const void* 
   const int d = shape->d, ffn = shape->ffn, n1 = w.n1;
   const bool swiglu = shape->act == LZ_SWIGLU;
 
-  hipLaunchKernelGGL(virtual_rows_kernel, dim3(1), dim3(256), 0, st, S, d, n1, w.virt_w2, w.virt_w1);
+  hipLaunchKernelGGL(virtual_rows_kernel, dim3(1), dim3(256), 0, st, S, ffn, d, w.virt_w2, w.virt_w1);
   int32_t r = lz::launch_status();
   if (r != LZ_OK) return r;
   TileTable t_rows, t_w2, t_w1;
   if ((r = build_table(slot_offsets, S, P, ceil_div(ffn, BN), d / BN, w.tiles_bwd, st, &t_rows)) != LZ_OK) return r;
-  if ((r = build_table(w.virt_w2, S, (long long)S * d, ceil_div(ffn, BN), 0, w.tiles_w2, st, &t_w2)) != LZ_OK) return r;
-  if ((r = build_table(w.virt_w1, S, (long long)S * n1, d / BN, 0, w.tiles_w1, st, &t_w1)) != LZ_OK) return r;
+  if ((r = build_table(w.virt_w2, S, (long long)S * ffn, d / BN, 0, w.tiles_w2, st, &t_w2)) != LZ_OK) return r;
+  if ((r = build_table(w.virt_w1, S, (long long)S * d, ceil_div(n1, BN), 0, w.tiles_w1, st, &t_w1)) != LZ_OK) return r;
 
   if (P > 0) {
-    // dH = dyp W2      (W2 [d, ffn]: contraction over its rows)
-    if ((r = gemm_dgrad((const uint16_t*)dyp, (const uint16_t*)w2, w.dh, P, d, ffn, 0, t_rows, st)) != LZ_OK) return r;
+    // dH = dyp W2^T    (W2 [ffn, d]: contraction along its rows)
+    if ((r = gemm_nt((const uint16_t*)dyp, (const uint16_t*)w2, w.dh, P, d, ffn, 0, t_rows, st)) != LZ_OK) return r;
     // dZ = dH * act'(Z)
     const int ffn_vec = ffn / 8;
     const unsigned blocks = (unsigned)((P * ffn_vec + 255) / 256);
@@ -447,14 +450,14 @@ extern "C" int32_t lz_ffn_backward(const void* dyp, const void* xp, const void* 
       hipLaunchKernelGGL(act_backward_kernel<false>, dim3(blocks), dim3(256), 0, st, (const u32x4*)w.dh,
                          (const u32x4*)z, P, ffn_vec, (u32x4*)w.dz);
     if ((r = lz::launch_status()) != LZ_OK) return r;
-    // dxp = dZ W1      (W1 [n1, d])
-    if ((r = gemm_dgrad(w.dz, (const uint16_t*)w1, (uint16_t*)dxp, P, n1, d, 1, t_rows, st)) != LZ_OK) return r;
+    // dxp = dZ W1^T    (W1 [d, n1])
+    if ((r = gemm_nt(w.dz, (const uint16_t*)w1, (uint16_t*)dxp, P, n1, d, 1, t_rows, st)) != LZ_OK) return r;
   }
-  // dW2[s] = dyp_s^T H_s,  dW1[s] = dZ_s^T xp_s
-  if ((r = gemm_wgrad((const uint16_t*)dyp, (const uint16_t*)h, (uint16_t*)dw2, S, P, d, ffn, slot_offsets, t_w2,
+  // dW2[s] = H_s^T dyp_s  [ffn, d],   dW1[s] = xp_s^T dZ_s  [d, n1]
+  if ((r = gemm_wgrad((const uint16_t*)h, (const uint16_t*)dyp, (uint16_t*)dw2, S, P, ffn, d, slot_offsets, t_w2,
                       st)) != LZ_OK)
     return r;
-  return gemm_wgrad(w.dz, (const uint16_t*)xp, (uint16_t*)dw1, S, P, n1, d, slot_offsets, t_w1, st);
+  return gemm_wgrad((const uint16_t*)xp, w.dz, (uint16_t*)dw1, S, P, d, n1, slot_offsets, t_w1, st);
 }
 
 extern "C" int32_t lz_reduce_replica_grads(const void* dw_slot, const int32_t* slot_expert, int32_t S, int32_t E,

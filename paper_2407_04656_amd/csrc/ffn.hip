@@ -1,8 +1,8 @@
 // Expert FFN as a grouped GEMM over the per-slot row ranges (Sec. 2.1: experts are
 // parallel FFNs; every replica processes the rows dispatched to its slot).
 //
-//   GEMM-1   hidden[P, ffn] = act(xp[P, d] * W1[slot]^T)      act = GELU | SwiGLU, fused
-//   GEMM-2   yp[P, d]       = hidden[P, ffn] * W2[slot]^T
+//   GEMM-1   hidden[P, ffn] = act(xp[P, d] * W1[slot])        act = GELU | SwiGLU, fused;  W1[slot] = [d, n1]
+//   GEMM-2   yp[P, d]       = hidden[P, ffn] * W2[slot]                                        W2[slot] = [ffn, d]
 //
 // Group sizes are data dependent and only known on the device, so a one-workgroup kernel
 // first turns slot_offsets into a table of row tiles (slot, first row, end row) and, for the
@@ -37,12 +37,11 @@ __device__ __forceinline__ void store_elem<float>(float* p, float v) { *p = v; }
 template <>
 __device__ __forceinline__ void store_elem<uint16_t>(uint16_t* p, float v) { *p = lz::f32_to_bf16(v); }
 
-// C[rows of the tile, n] = epi( sum_k A[row, k] * W[slot][n (+ n_up), k] )
+// C[rows of the tile, n] = epi( sum_k A[row, k] * W[slot][k, n (+ up_col0)] ),  W[slot] = [K, ldw]
 template <typename Elem, int EPI>
 __global__ __launch_bounds__(256) void gemm_generic_kernel(const Elem* __restrict__ A, int K,
-                                                           const Elem* __restrict__ W,
-                                                           size_t w_slot_stride, int n_out, int up_row0,
-                                                           Elem* __restrict__ C, TileTable t) {
+                                                           const Elem* __restrict__ W, int ldw, int n_out,
+                                                           int up_col0, Elem* __restrict__ C, TileTable t) {
   constexpr int BM = 64, BN = 64, BK = 16;
   constexpr bool DUAL = EPI == EPI_SWIGLU;
   __shared__ float sA[BK][BM + 1];
@@ -52,7 +51,7 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(const Elem* __restric
   const int slot = t.slot[tile], row0 = t.row0[tile], row_end = t.row_end[tile];
   if (slot < 0) return;
   const int n0 = blockIdx.x * BN;
-  const Elem* Ws = W + (size_t)slot * w_slot_stride;
+  const Elem* Ws = W + (size_t)slot * K * ldw;
   const int tx = threadIdx.x % 16, ty = threadIdx.x / 16;
   float acc[4][4] = {}, acc_up[4][4] = {};
   for (int k0 = 0; k0 < K; k0 += BK) {
@@ -60,10 +59,13 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(const Elem* __restric
       const int r = i / BK, kk = i % BK;
       const int row = row0 + r;
       sA[kk][r] = (row < row_end && k0 + kk < K) ? load_elem<Elem>(A + (size_t)row * K + k0 + kk) : 0.f;
-      const int n = n0 + r;
+    }
+    for (int i = threadIdx.x; i < BN * BK; i += 256) {
+      const int c = i % BN, kk = i / BN;  // consecutive threads read consecutive columns of a weight row
+      const int n = n0 + c;
       const bool ok = n < n_out && k0 + kk < K;
-      sB[0][kk][r] = ok ? load_elem<Elem>(Ws + (size_t)n * K + k0 + kk) : 0.f;
-      if (DUAL) sB[DUAL ? 1 : 0][kk][r] = ok ? load_elem<Elem>(Ws + (size_t)(up_row0 + n) * K + k0 + kk) : 0.f;
+      sB[0][kk][c] = ok ? load_elem<Elem>(Ws + (size_t)(k0 + kk) * ldw + n) : 0.f;
+      if (DUAL) sB[DUAL ? 1 : 0][kk][c] = ok ? load_elem<Elem>(Ws + (size_t)(k0 + kk) * ldw + up_col0 + n) : 0.f;
     }
     __syncthreads();
 #pragma unroll
@@ -186,24 +188,23 @@ extern "C" int32_t lz_ffn_up(const void* xp, const void* w1, const lz_shape* sha
     if (shape->dtype == LZ_F32) {
       if (swiglu)
         hipLaunchKernelGGL((gemm_generic_kernel<float, EPI_SWIGLU>), grid, dim3(256), 0, st, (const float*)xp,
-                           shape->d, (const float*)w1, (size_t)n1 * shape->d, shape->ffn, shape->ffn,
-                           (float*)w.hidden, t);
+                           shape->d, (const float*)w1, n1, shape->ffn, shape->ffn, (float*)w.hidden, t);
       else
         hipLaunchKernelGGL((gemm_generic_kernel<float, EPI_GELU>), grid, dim3(256), 0, st, (const float*)xp,
-                           shape->d, (const float*)w1, (size_t)n1 * shape->d, shape->ffn, 0,
-                           (float*)w.hidden, t);
+                           shape->d, (const float*)w1, n1, shape->ffn, 0, (float*)w.hidden, t);
     } else {
       if (swiglu)
         hipLaunchKernelGGL((gemm_generic_kernel<uint16_t, EPI_SWIGLU>), grid, dim3(256), 0, st,
-                           (const uint16_t*)xp, shape->d, (const uint16_t*)w1, (size_t)n1 * shape->d,
-                           shape->ffn, shape->ffn, (uint16_t*)w.hidden, t);
+                           (const uint16_t*)xp, shape->d, (const uint16_t*)w1, n1, shape->ffn, shape->ffn,
+                           (uint16_t*)w.hidden, t);
       else
         hipLaunchKernelGGL((gemm_generic_kernel<uint16_t, EPI_GELU>), grid, dim3(256), 0, st,
-                           (const uint16_t*)xp, shape->d, (const uint16_t*)w1, (size_t)n1 * shape->d,
-                           shape->ffn, 0, (uint16_t*)w.hidden, t);
+                           (const uint16_t*)xp, shape->d, (const uint16_t*)w1, n1, shape->ffn, 0,
+                           (uint16_t*)w.hidden, t);
     }
     return lz::launch_status();
   }
+  if ((uintptr_t)xp % 16 != 0 || (uintptr_t)w1 % 16 != 0) return LZ_EINVAL;  // 16-byte loads per lane
   MfmaArgs g1{};
   g1.A = (const uint16_t*)xp;
   g1.W = (const uint16_t*)w1;
@@ -216,7 +217,8 @@ extern "C" int32_t lz_ffn_up(const void* xp, const void* w1, const lz_shape* sha
   g1.n_tiles = w.n_up;
   g1.which = 0;
   g1.t = t;
-  return swiglu ? launch_mfma<EPI_SWIGLU>(g1, st) : launch_mfma<EPI_GELU>(g1, st);
+  g1.ldw = n1;
+  return swiglu ? launch_mfma<EPI_SWIGLU, MODE_NN>(g1, st) : launch_mfma<EPI_GELU, MODE_NN>(g1, st);
 }
 
 extern "C" int32_t lz_ffn_down(const void* w2, const lz_shape* shape, void* yp, void* ws,
@@ -233,15 +235,15 @@ extern "C" int32_t lz_ffn_down(const void* w2, const lz_shape* shape, void* yp, 
     const dim3 grid((shape->d + 63) / 64, t.capacity);
     if (shape->dtype == LZ_F32)
       hipLaunchKernelGGL((gemm_generic_kernel<float, EPI_NONE>), grid, dim3(256), 0, st,
-                         (const float*)w.hidden, shape->ffn, (const float*)w2,
-                         (size_t)shape->d * shape->ffn, shape->d, 0, (float*)yp, t);
+                         (const float*)w.hidden, shape->ffn, (const float*)w2, shape->d, shape->d, 0,
+                         (float*)yp, t);
     else
       hipLaunchKernelGGL((gemm_generic_kernel<uint16_t, EPI_NONE>), grid, dim3(256), 0, st,
-                         (const uint16_t*)w.hidden, shape->ffn, (const uint16_t*)w2,
-                         (size_t)shape->d * shape->ffn, shape->d, 0, (uint16_t*)yp, t);
+                         (const uint16_t*)w.hidden, shape->ffn, (const uint16_t*)w2, shape->d, shape->d, 0,
+                         (uint16_t*)yp, t);
     return lz::launch_status();
   }
-  if ((uintptr_t)yp % 16 != 0) return LZ_EINVAL;  // the MFMA epilogue stores 16 bytes per lane
+  if ((uintptr_t)yp % 16 != 0 || (uintptr_t)w2 % 16 != 0) return LZ_EINVAL;  // 16-byte accesses per lane
   MfmaArgs g2{};
   g2.A = (const uint16_t*)w.hidden;
   g2.W = (const uint16_t*)w2;
@@ -254,7 +256,8 @@ extern "C" int32_t lz_ffn_down(const void* w2, const lz_shape* shape, void* yp, 
   g2.n_tiles = w.n_down;
   g2.which = 1;
   g2.t = t;
-  return launch_mfma<EPI_NONE>(g2, st);
+  g2.ldw = shape->d;
+  return launch_mfma<EPI_NONE, MODE_NN>(g2, st);
 }
 
 extern "C" int32_t lz_expert_ffn(const void* xp, const int32_t* slot_offsets, const void* w1,

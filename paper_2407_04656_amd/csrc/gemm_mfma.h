@@ -1,20 +1,22 @@
 // Grouped bf16 GEMM on the gfx950 matrix cores and the row-tile table it draws its work from;
 // shared by the forward and the backward translation units (device code, not part of the C ABI).
 //
-//   C[rows of a slot, n] = epi( sum_k A[row, k] * W[slot][n, k] )      both operands K-contiguous
+//   C[rows of a slot, n] = epi( sum_k A(row, k) * W[slot](n, k) )
 //
-// bf16 path (gfx950 MFMA): persistent kernel, one workgroup per CU, drawing 256x256 tiles from
-// its XCD's queue.  4 waves in 2x2, each wave a 128x128 patch = 4x4
-// v_mfma_f32_32x32x16_bf16 accumulators (fp32, 256 AGPRs).  Both operands are K-contiguous
-// and are streamed HBM -> LDS with 16-byte buffer loads that write LDS directly, through two
-// LDS stages of 64 K-columns; fragment reads are software pipelined over two register sets.
-// The XOR swizzle that keeps the ds_read_b128 fragment reads conflict-free is applied on the
-// global-address side because a direct-to-LDS load fixes the LDS side to lane order.  Buffer
-// descriptors bound every load, so ragged tiles cannot fault.  The MFMA takes the weight
-// fragment as its row operand, which leaves each lane with 4 consecutive output columns per
-// accumulator group: 8-byte bf16 stores, no LDS transpose.  For SwiGLU the weight tile
-// interleaves 32-row fragments of Wg and Wu, so the gate and up values of one output element
-// sit in the same lane and register index.
+// Persistent kernel, one workgroup per CU, drawing 256x256 tiles from its XCD's queue.  4 waves
+// in 2x2, each wave a 128x128 patch = 4x4 v_mfma_f32_32x32x16_bf16 accumulators (fp32, 256
+// AGPRs).  Operand tiles are streamed HBM -> LDS with 16-byte buffer loads that write LDS
+// directly, through two LDS stages of 64 k; fragment reads are software pipelined over two
+// register sets.  An operand may be k-contiguous ([row, k]: 256 tile rows of 128 B, read with
+// ds_read_b128) or k-major ([k, column]: 64 k-rows of 512 B, read with the transposing
+// ds_read_b64_tr_b16); see the MODE_* list below.  The XOR swizzles that keep the fragment
+// reads free of bank conflicts are applied on the global-address side, because a direct-to-LDS
+// load fixes the LDS side to lane order.  Buffer descriptors bound every load, so ragged tiles
+// cannot fault.  The MFMA takes the weight fragment as its row operand, which leaves each lane
+// with 4 consecutive output columns per accumulator group; the epilogue regroups them through
+// a per-wave LDS patch into whole 128-byte lines.  For SwiGLU the weight tile interleaves
+// 32-wide fragments of the gate and the up projection, so the gate and up values of one output
+// element sit in the same lane and register index.
 #pragma once
 #include "lz_common.h"
 
@@ -165,7 +167,7 @@ constexpr int kLdsBytes = 2 * kStageBytes;         // two stages: 128 KiB of the
 
 struct MfmaArgs {
   const uint16_t* A;    // [P, K]
-  const uint16_t* W;    // [S, w_rows, K]
+  const uint16_t* W;    // MODE_NT: [S, w_rows, K];  MODE_NN: [S, K, ldw];  MODE_TN: [k_rows, ldw]
   uint16_t* C;          // [P, n_out]
   long long P;
   int K;
@@ -175,7 +177,7 @@ struct MfmaArgs {
   int n_tiles;          // column tiles per row tile
   int which;            // 0 = GEMM-1, 1 = GEMM-2: which unit lists and tickets of the tile table
   TileTable t;
-  // MODE_NN (data gradients): W is [S, K, ldw], the contraction runs over its rows.
+  // MODE_NN (forward): W is [S, K, ldw], the contraction runs over its rows.
   // MODE_TN (weight gradients): both operands are K-major, A [k_rows, lda] and W [k_rows, ldw];
   // slot s contracts over their rows [slot_offsets[s], slot_offsets[s+1]) and owns rows_per_slot
   // rows of C (row index = s * rows_per_slot + m, m = column of A).
@@ -186,8 +188,8 @@ struct MfmaArgs {
 };
 
 // Operand layouts of the contraction C[m, n] = sum_k A(m, k) W(n, k):
-//   MODE_NT  A [m, k], W [n, k]: both contiguous along k (the forward)
-//   MODE_NN  A [m, k], W [k, n]
+//   MODE_NT  A [m, k], W [n, k]: both contiguous along k (the data gradients)
+//   MODE_NN  A [m, k], W [k, n] (the forward: weights are stored input-major)
 //   MODE_TN  A [k, m], W [k, n], a different k range for every slot
 // A k-major operand tile lies in LDS as 64 k-rows of 256 columns (512 B each) and is read with
 // ds_read_b64_tr_b16, which hands every lane four k-values of one column: the 16 lanes of a
@@ -347,7 +349,14 @@ __device__ __forceinline__ void gemm_tile(const MfmaArgs& a, char* smem, int slo
   }
 #pragma unroll
   for (int i = 0; i < kLoadsW; ++i) {
-    if constexpr (TB) {
+    if constexpr (TB && EPI == EPI_SWIGLU) {
+      // k-major SwiGLU weights [K, 2 ffn]: 32-column fragments alternate gate and up columns
+      const int kr = (wave * 8 + i) * 2 + (lane >> 5);
+      const int piece = (lane & 31) ^ ((kr & 3) << 2);
+      const int f = piece >> 2;
+      const int col = n0 + (f >> 1) * 32 + (piece & 3) * 8 + ((f & 1) ? a.up_row0 : 0);
+      voffW[i] = (int)(((uint32_t)kr * (uint32_t)a.ldw + (uint32_t)col) * 2u);
+    } else if constexpr (TB) {
       voffW[i] = voff_kmajor(i, a.ldw, MODE == MODE_NN ? n0 : 0);
     } else {
       const int r = (wave * kLoadsW + i) * 8 + (lane >> 3);

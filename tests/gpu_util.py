@@ -17,6 +17,14 @@ def to_dev(a, bf16=False):
     return t.to(DEV)
 
 
+def slot_weights(w, slot_expert, bf16):
+    """Device copies of every slot's expert weights in the library's input-major layout:
+    w1 [S, d, n1], w2 [S, ffn, d] (the host arrays are [out, in])."""
+    w1 = np.ascontiguousarray(np.asarray(w["w1"])[slot_expert].transpose(0, 2, 1))
+    w2 = np.ascontiguousarray(np.asarray(w["w2"])[slot_expert].transpose(0, 2, 1))
+    return to_dev(w1, bf16), to_dev(w2, bf16)
+
+
 def to_host(t):
     if t.dtype == torch.bfloat16:
         return t.view(torch.uint16).cpu().numpy()

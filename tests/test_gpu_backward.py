@@ -10,7 +10,7 @@ from oracle import moe_layer as om
 from workloads import CONFIGS, expert_weights, f32_to_bf16_bits, step_inputs
 from workloads.configs import scaled
 
-from gpu_util import DEV, oracle_plan, rel_err, to_dev, to_host
+from gpu_util import DEV, oracle_plan, rel_err, slot_weights, to_dev, to_host
 
 pytestmark = pytest.mark.gpu
 
@@ -34,7 +34,7 @@ def _ffn_backward_case(cfg, counts, seed):
     dyph = _bf16(rng, (P, cfg.d), 0.5)
     shape = lz.Shape.from_config(cfg)
     bf = torch.bfloat16
-    w1, w2 = to_dev(w["w1"][slot_expert], True), to_dev(w["w2"][slot_expert], True)
+    w1, w2 = slot_weights(w, slot_expert, True)
     nbytes = lz.lz_train_workspace_bytes(shape)
     assert nbytes > 0
     ws = torch.empty(nbytes, dtype=torch.uint8, device=DEV)
@@ -44,8 +44,8 @@ def _ffn_backward_case(cfg, counts, seed):
     yp = torch.zeros((P, cfg.d), dtype=bf, device=DEV)
     lz.lz_ffn_forward_train(xp, off, w1, w2, shape, z, h, yp, ws, nbytes)
     dxp = torch.zeros((P, cfg.d), dtype=bf, device=DEV)
-    dw1 = torch.full((S, n1, cfg.d), 7.0, dtype=bf, device=DEV)
-    dw2 = torch.full((S, cfg.d, cfg.ffn), 7.0, dtype=bf, device=DEV)
+    dw1 = torch.full((S, cfg.d, n1), 7.0, dtype=bf, device=DEV)       # gradients in the weights' layout
+    dw2 = torch.full((S, cfg.ffn, cfg.d), 7.0, dtype=bf, device=DEV)
     lz.lz_ffn_backward(dyp, xp, z, h, off, w1, w2, shape, dxp, dw1, dw2, ws, nbytes)
     torch.cuda.synchronize()
 
@@ -60,6 +60,7 @@ def _ffn_backward_case(cfg, counts, seed):
     assert rel_err(to_host(yp), om.expert_ffn_rows(xph, offsets, slot_expert, w["w1"], w["w2"], cfg.act)) <= TOL
     # backward
     dxp_ref, dw1_ref, dw2_ref = ob.ffn_backward_rows(dyph, xph, offsets, slot_expert, w["w1"], w["w2"], cfg.act)
+    dw1_ref, dw2_ref = dw1_ref.transpose(0, 2, 1), dw2_ref.transpose(0, 2, 1)   # oracle: [out, in]
     assert rel_err(to_host(dxp), dxp_ref) <= TOL
     assert rel_err(to_host(dw1), dw1_ref) <= TOL
     assert rel_err(to_host(dw2), dw2_ref) <= TOL
@@ -154,8 +155,8 @@ def test_layer_backward_end_to_end(act):
                             disp["slot_offsets"], plan, w["w1"], w["w2"], act)
     assert rel_err(to_host(layer.dx), ref["dx"]) <= TOL
     assert rel_err(to_host(layer.dgates), ref["dgates"]) <= TOL
-    assert rel_err(to_host(layer.dw1), ref["dw1"]) <= TOL
-    assert rel_err(to_host(layer.dw2), ref["dw2"]) <= TOL
+    assert rel_err(to_host(layer.dw1), ref["dw1"].transpose(0, 2, 1)) <= TOL     # oracle: [out, in]
+    assert rel_err(to_host(layer.dw2), ref["dw2"].transpose(0, 2, 1)) <= TOL
     dl_ref = ob.route_backward(ref["dgates"], gates, ids, cfg.E)
     assert rel_err(to_host(layer.dlogits), dl_ref) <= TOL
     # a second pass on the same buffers gives the same bits (queues and scratch are reset)
@@ -206,8 +207,8 @@ def test_full_config_backward(name):
         dxp_ref, dw1_ref, dw2_ref = ob.ffn_backward_slot(om.widen(dyp_dev[a:b]), om.widen(xp_dev[a:b]),
                                                         om.widen(w["w1"][e]), om.widen(w["w2"][e]), cfg.act)
         assert rel_err(dxp_dev[a:b], dxp_ref) <= TOL, (s, "dxp")
-        assert rel_err(to_host(layer.dw1_slot[s]), dw1_ref) <= TOL, (s, "dw1")
-        assert rel_err(to_host(layer.dw2_slot[s]), dw2_ref) <= TOL, (s, "dw2")
+        assert rel_err(to_host(layer.dw1_slot[s]), dw1_ref.T) <= TOL, (s, "dw1")
+        assert rel_err(to_host(layer.dw2_slot[s]), dw2_ref.T) <= TOL, (s, "dw2")
     for s in np.nonzero(counts == 0)[0][:2]:
         assert not layer.dw1_slot[int(s)].any().item() and not layer.dw2_slot[int(s)].any().item()
     # permute backward on all tokens from the device's own dxp; replica sums for one expert

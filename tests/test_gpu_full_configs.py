@@ -129,15 +129,15 @@ def test_post_failure_replan():
     old_layer.load_expert_weights(w["w1"], w["w2"], old_plan)
     layer = lz.MoELayer(shape_new, DEV)
     n1 = w["w1"].shape[1]
-    layer.w1 = torch.zeros((shape_new.S, n1, cfg.d), dtype=torch.bfloat16, device=DEV)
-    layer.w2 = torch.zeros((shape_new.S, cfg.d, cfg.ffn), dtype=torch.bfloat16, device=DEV)
+    layer.w1 = torch.zeros((shape_new.S, cfg.d, n1), dtype=torch.bfloat16, device=DEV)    # input-major
+    layer.w2 = torch.zeros((shape_new.S, cfg.ffn, cfg.d), dtype=torch.bfloat16, device=DEV)
     lz.lz_apply_transfers(got_re["transfers"], old_layer.w1, old_layer.w2, shape_old.S, layer.w1, layer.w2,
                           shape_new.S, shape_new)
     torch.cuda.synchronize()
     for slot in (0, 17, shape_new.S - 1):
         e = int(new_plan[slot])
-        assert np.array_equal(to_host(layer.w1[slot]), w["w1"][e])
-        assert np.array_equal(to_host(layer.w2[slot]), w["w2"][e])
+        assert np.array_equal(to_host(layer.w1[slot]), w["w1"][e].T)
+        assert np.array_equal(to_host(layer.w2[slot]), w["w2"][e].T)
     del old_layer
     torch.cuda.empty_cache()
 

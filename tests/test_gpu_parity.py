@@ -15,7 +15,7 @@ from oracle import planner as op
 from workloads import CONFIGS, expert_weights, f32_to_bf16_bits, step_inputs
 from workloads.configs import scaled
 
-from gpu_util import (DEV, check_dispatch_exact, oracle_plan, rel_err, run_layer, to_dev, to_host,
+from gpu_util import (DEV, check_dispatch_exact, oracle_plan, rel_err, run_layer, slot_weights, to_dev, to_host,
                       tolerance)
 
 pytestmark = pytest.mark.gpu
@@ -197,8 +197,7 @@ def _ffn_case(cfg, counts, seed):
     xph = f32_to_bf16_bits(xp) if bf16 else xp
     shape = lz.Shape.from_config(cfg)
     tdt = torch.bfloat16 if bf16 else torch.float32
-    w1 = to_dev(w["w1"][slot_expert], bf16)
-    w2 = to_dev(w["w2"][slot_expert], bf16)
+    w1, w2 = slot_weights(w, slot_expert, bf16)
     yp = torch.zeros((cfg.T * cfg.k, cfg.d), dtype=tdt, device=DEV)
     nbytes = lz.lz_ffn_workspace_bytes(shape)
     ws = torch.empty(nbytes, dtype=torch.uint8, device=DEV)
@@ -246,7 +245,7 @@ def test_expert_ffn_stages_can_be_repeated_on_one_tile_table():
     w = expert_weights(cfg, threads=4)
     xph = f32_to_bf16_bits(rng.standard_normal((cfg.T * cfg.k, cfg.d)).astype(np.float32))
     shape = lz.Shape.from_config(cfg)
-    w1, w2 = to_dev(w["w1"][slot_expert], True), to_dev(w["w2"][slot_expert], True)
+    w1, w2 = slot_weights(w, slot_expert, True)
     xp, off = to_dev(xph, True), to_dev(offsets)
     nbytes = lz.lz_ffn_workspace_bytes(shape)
     ws = torch.empty(nbytes, dtype=torch.uint8, device=DEV)
@@ -271,7 +270,7 @@ def test_expert_ffn_clips_bad_offsets():
     ws = torch.empty(nbytes, dtype=torch.uint8, device=DEV)
     xp = torch.zeros((512, 256), dtype=torch.bfloat16, device=DEV)
     w1 = torch.zeros((4, 256, 256), dtype=torch.bfloat16, device=DEV)
-    w2 = torch.zeros((4, 256, 128), dtype=torch.bfloat16, device=DEV)
+    w2 = torch.zeros((4, 128, 256), dtype=torch.bfloat16, device=DEV)
     yp = torch.ones((512, 256), dtype=torch.bfloat16, device=DEV)
     bad = to_dev(np.array([-50, 100, 90, 100000, 7], dtype=np.int32))
     lz.lz_expert_ffn(xp, bad, w1, w2, shape, yp, ws, nbytes)
