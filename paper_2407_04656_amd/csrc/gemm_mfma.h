@@ -423,12 +423,13 @@ __device__ __forceinline__ void gemm_tile(const MfmaArgs& a, char* smem, int slo
   // wave has waited for before the barrier) can be read.
   //
   // The loads of step kt+2 are not issued in one burst: a wave that issues a burst stands still
-  // until the texture unit has accepted it, and the MFMA pipe with it.  Six go out during the
-  // slice after barrier kt, the rest during slice 0 of step kt+1, none in slices 1 and 2, which
-  // leaves every load two slices to land before the wait at the end of step kt+1; the
-  // activation loads go first.  (Measured on three workloads: 6 + rest + 0 beats 8 + half + half
-  // by 2-11 %, and 4, 5, 7, 8, 10, 12 or all 16 after the barrier; activations first is 0.7 %
-  // ahead of weights first on the first GEMM and level on the second.)
+  // until the texture unit has accepted it, and the MFMA pipe with it.  Six (eight when an
+  // operand is k-major) go out during the slice after barrier kt, the rest during slice 0 of
+  // step kt+1, none in slices 1 and 2, which leaves every load two slices to land before the
+  // wait at the end of step kt+1; the activation loads go first.  (Measured on three workloads with k-contiguous operands: 6 + rest
+  // + 0 beats 8 + half + half by 2-11 %, and 4, 5, 7, 8, 10, 12 or all 16 after the barrier;
+  // activations first is 0.7 % ahead of weights first on the first GEMM and level on the second.
+  // With k-major weights 8 after the barrier is 0.5-2 % ahead of 6, 10 level, 4, 12 and 16 behind.)
   const int k_steps = (K + BK - 1) / BK;
   constexpr int kLoads = kLoadsW + kLoadsX;
   auto issue = [&](int stage, int step, int q0, int q1) {
@@ -462,7 +463,8 @@ __device__ __forceinline__ void gemm_tile(const MfmaArgs& a, char* smem, int slo
     }
   };
   constexpr int kDsReads = (TB ? 8 : 4) + (TA ? 2 * XF : XF);  // LDS read instructions per slice
-  constexpr int kAfterBarrier = 6;                 // loads issued in the slice after the barrier,
+  constexpr int kWanted = MODE == MODE_NT ? 6 : 8;
+  constexpr int kAfterBarrier = kWanted < kLoads ? kWanted : kLoads;  // loads issued in the slice after the barrier,
   constexpr int kSlice0 = kLoads - kAfterBarrier;  // and in slice 0 of the next step
   bf16x8 xf[2][XF], wf[2][4];
   // read order = order of first use by the MFMAs (weight fragment 0, all activation fragments,
