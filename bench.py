@@ -27,7 +27,7 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 # HBM bytes per launch of the dominant kernel, from the rocprofv3 FETCH_SIZE / WRITE_SIZE passes
 # summarised in profiles/<workload>_hbm_traffic.md (counters cannot be read from inside this
 # process, so the figure is carried here and re-measured whenever the kernel changes).
-MEASURED_TRAFFIC_BYTES = {"c2_mixtral": 14.26e9}
+MEASURED_TRAFFIC_BYTES = {"c2_mixtral": 14.39e9}
 
 
 def parse():
