@@ -122,3 +122,42 @@ def test_device_calls_validate_arguments_without_a_gpu():
     with pytest.raises(lz.LzError) as ei:
         lz.lz_permute(None, None, bad, None, stream=0)
     assert ei.value.code == -2
+
+
+def test_training_calls_validate_arguments_without_a_gpu():
+    def shape(**kw):
+        base = dict(T=512, d=256, ffn=128, E=8, k=2, N=2, c=4, dtype=lz.LZ_BF16, act=lz.LZ_SWIGLU)
+        base.update(kw)
+        return lz.Shape(**base)
+
+    ok = shape()
+    n = lz.lz_train_workspace_bytes(ok)
+    # at least the two gradient intermediates dH [P, ffn] and dZ [P, 2 ffn]
+    assert n >= ok.P * ok.ffn * 2 + ok.P * 2 * ok.ffn * 2
+    for bad in (shape(dtype=lz.LZ_F32), shape(d=264), shape(ffn=100), shape(k=9),
+                shape(T=1 << 20, k=8, d=4096, ffn=14336)):          # 32-bit offsets into a slot's rows
+        assert lz.lz_train_workspace_bytes(bad) == 0
+        with pytest.raises(lz.LzError) as ei:
+            lz.lz_ffn_backward(None, None, None, None, None, None, None, bad, None, None, None, None, 0, stream=0)
+        assert ei.value.code == -2
+        with pytest.raises(lz.LzError) as ei:
+            lz.lz_ffn_forward_train(None, None, None, None, bad, None, None, None, None, 0, stream=0)
+        assert ei.value.code == -2
+    with pytest.raises(lz.LzError) as ei:                            # no workspace
+        lz.lz_ffn_backward(None, None, None, None, None, None, None, ok, None, None, None, None, n, stream=0)
+    assert ei.value.code == -3
+    with pytest.raises(lz.LzError) as ei:                            # null tensors
+        lz.lz_combine_backward(None, None, None, None, ok, None, None, stream=0)
+    assert ei.value.code == -1
+    with pytest.raises(lz.LzError) as ei:
+        lz.lz_combine_backward(None, None, None, None, shape(dtype=lz.LZ_F32), None, None, stream=0)
+    assert ei.value.code == -2
+    with pytest.raises(lz.LzError) as ei:
+        lz.lz_route_backward(None, None, None, ok, None, stream=0)
+    assert ei.value.code == -1
+    with pytest.raises(lz.LzError) as ei:
+        lz.lz_reduce_replica_grads(None, None, 4, 2, 12, None, stream=0)   # not a multiple of 8 elements
+    assert ei.value.code == -2
+    with pytest.raises(lz.LzError) as ei:
+        lz.lz_permute_backward(None, None, ok, None, stream=0)
+    assert ei.value.code == -1
