@@ -166,22 +166,21 @@ constexpr int kStageBytes = (BM + BN) * kRowBytes; // activation tile (up to 256
 constexpr int kLdsBytes = 2 * kStageBytes;         // two stages: 128 KiB of the CU's 160 KiB
 
 struct MfmaArgs {
-  const uint16_t* A;    // [P, K]
+  const uint16_t* A;    // MODE_NT, MODE_NN: [P, K];  MODE_TN: [k_rows, lda]
   const uint16_t* W;    // MODE_NT: [S, w_rows, K];  MODE_NN: [S, K, ldw];  MODE_TN: [k_rows, ldw]
   uint16_t* C;          // [P, n_out]
-  long long P;
-  int K;
-  int w_rows;           // weight rows per slot
+  long long P;          // rows of C (MODE_TN: S * rows_per_slot virtual rows)
+  int K;                // contraction length (MODE_TN: per slot, from slot_offsets)
+  int w_rows;           // MODE_NT: weight rows per slot
   int n_out;            // output columns
-  int up_row0;          // SwiGLU: first row of the up projection inside a slot's W
+  int up_row0;          // SwiGLU: offset of the up projection inside a slot's W (rows, or columns if k-major)
   int n_tiles;          // column tiles per row tile
-  int which;            // 0 = GEMM-1, 1 = GEMM-2: which unit lists and tickets of the tile table
+  int which;            // which of the tile table's two unit lists and ticket sets this launch draws from
   TileTable t;
-  // MODE_NN (forward): W is [S, K, ldw], the contraction runs over its rows.
-  // MODE_TN (weight gradients): both operands are K-major, A [k_rows, lda] and W [k_rows, ldw];
-  // slot s contracts over their rows [slot_offsets[s], slot_offsets[s+1]) and owns rows_per_slot
-  // rows of C (row index = s * rows_per_slot + m, m = column of A).
-  int lda, ldw;
+  // MODE_TN (weight gradients): slot s contracts over the rows [slot_offsets[s], slot_offsets[s+1])
+  // of both operands and owns rows_per_slot rows of C (row index = s * rows_per_slot + m, m =
+  // column of A).
+  int lda, ldw;         // row strides (elements) of the k-major operands
   const int32_t* slot_offsets;
   long long k_rows;
   int rows_per_slot;
