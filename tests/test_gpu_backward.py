@@ -167,7 +167,7 @@ def test_layer_backward_end_to_end(act):
         assert torch.equal(a.view(torch.int16), b.view(torch.int16))
 
 
-@pytest.mark.parametrize("name", ["c3_gptmoe", "c4_finegrained"])
+@pytest.mark.parametrize("name", ["c2_mixtral", "c3_gptmoe", "c4_finegrained"])
 def test_full_config_backward(name):
     """Full size, in the launch configuration the timing runs use: the largest, the smallest
     non-empty, a middle and an empty slot are checked completely (dxp rows, both weight
