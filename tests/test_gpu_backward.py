@@ -222,6 +222,63 @@ def test_full_config_backward(name):
     assert np.allclose(to_host(layer.dlogits), dl_ref, rtol=1e-4, atol=1e-5 * np.max(np.abs(dl_ref)))
 
 
+def test_backward_without_tokens_and_with_bad_offsets():
+    """T = 0: every call succeeds and the weight gradients are exact zeros.  Offsets outside
+    [0, P] or decreasing are clipped as in the forward: never an out-of-bounds access, and the
+    slots that stay valid still get their gradients."""
+    bf = torch.bfloat16
+    cfg0 = scaled(CONFIGS["c1_tiny"], act="gelu", dtype="bf16", T=0, k=2, d=256, ffn=256, N=2, c=2)
+    shape0 = lz.Shape.from_config(cfg0)
+    n = lz.lz_train_workspace_bytes(shape0)
+    assert n > 0
+    ws = torch.empty(n, dtype=torch.uint8, device=DEV)
+    S = 4
+    w1 = torch.ones((S, 256, 256), dtype=bf, device=DEV)
+    w2 = torch.ones((S, 256, 256), dtype=bf, device=DEV)
+    dw1 = torch.full((S, 256, 256), 3.0, dtype=bf, device=DEV)
+    dw2 = torch.full((S, 256, 256), 3.0, dtype=bf, device=DEV)
+    empty = torch.zeros((0, 256), dtype=bf, device=DEV)
+    off0 = torch.zeros(S + 1, dtype=torch.int32, device=DEV)
+    lz.lz_ffn_forward_train(empty, off0, w1, w2, shape0, empty, empty, empty, ws, n)
+    lz.lz_ffn_backward(empty, empty, empty, empty, off0, w1, w2, shape0, empty, dw1, dw2, ws, n)
+    lz.lz_combine_backward(empty, empty, off0, torch.zeros(0, device=DEV), shape0, empty, torch.zeros(0, device=DEV))
+    lz.lz_permute_backward(empty, off0, shape0, empty)
+    torch.cuda.synchronize()
+    assert not dw1.any().item() and not dw2.any().item()
+
+    cfg = scaled(cfg0, T=300)
+    shape = lz.Shape.from_config(cfg)
+    P = cfg.T * cfg.k
+    rng = np.random.default_rng(3)
+    w = expert_weights(cfg, threads=2)
+    slot_expert = np.array([0, 1, 2, 3], dtype=np.int32)
+    w1, w2 = slot_weights(w, slot_expert, True)
+    xph, dyph = _bf16(rng, (P, cfg.d)), _bf16(rng, (P, cfg.d), 0.5)
+    bad = np.array([-7, 200, 200, 700, 650], dtype=np.int32)     # clipped: [0,200) [200,200) [200,600) [600,600)
+    good = np.array([0, 200, 200, 600, 600], dtype=np.int32)
+    n = lz.lz_train_workspace_bytes(shape)
+    ws = torch.empty(n, dtype=torch.uint8, device=DEV)
+    outs = []
+    for off in (bad, good):
+        z = torch.zeros((P, cfg.ffn), dtype=bf, device=DEV)
+        h = torch.zeros((P, cfg.ffn), dtype=bf, device=DEV)
+        yp = torch.zeros((P, cfg.d), dtype=bf, device=DEV)
+        dxp = torch.zeros((P, cfg.d), dtype=bf, device=DEV)
+        dw1 = torch.full((S, cfg.d, cfg.ffn), 3.0, dtype=bf, device=DEV)
+        dw2 = torch.full((S, cfg.ffn, cfg.d), 3.0, dtype=bf, device=DEV)
+        lz.lz_ffn_forward_train(to_dev(xph, True), to_dev(off), w1, w2, shape, z, h, yp, ws, n)
+        lz.lz_ffn_backward(to_dev(dyph, True), to_dev(xph, True), z, h, to_dev(off), w1, w2, shape, dxp, dw1, dw2,
+                           ws, n)
+        torch.cuda.synchronize()
+        outs.append((yp, dxp, dw1, dw2))
+    for a_, b_ in zip(*outs):
+        assert torch.equal(a_.view(torch.int16), b_.view(torch.int16))
+    dxp_ref, dw1_ref, dw2_ref = ob.ffn_backward_rows(dyph, xph, good, slot_expert, w["w1"], w["w2"], cfg.act)
+    assert rel_err(to_host(outs[0][1])[:600], dxp_ref[:600]) <= TOL
+    assert rel_err(to_host(outs[0][2]), dw1_ref.transpose(0, 2, 1)) <= TOL
+    assert not outs[0][2][1].any().item() and not outs[0][3][3].any().item()      # the empty slots
+
+
 def test_training_entry_points_reject_what_they_do_not_serve():
     f32 = lz.Shape.from_config(CONFIGS["c1_tiny"])
     assert lz.lz_train_workspace_bytes(f32) == 0
