@@ -132,6 +132,14 @@ int32_t lz_permute(const void* x, const int32_t* row_to_pair, const lz_shape* sh
 int32_t lz_permute_scatter(const void* x, const int32_t* pair_to_row, const lz_shape* shape,
                            void* xp, void* stream);
 
+/* One-time conversion between the usual [out, in] weight layout and the input-major layout the
+ * FFN calls take (not on the timed path): packed[s][c][r] = w[s][r][c] for s < S, i.e.
+ * w dev [S, rows, cols] -> packed dev [S, cols, rows], any sizes, dtype LZ_F32 or LZ_BF16.
+ * w1 [S, n1, d] -> [S, d, n1] and w2 [S, d, ffn] -> [S, ffn, d]; applied to a gradient in the
+ * library's layout it gives the [out, in] form back.  The buffers must not overlap. */
+int32_t lz_pack_weights(const void* w, int32_t S, int32_t rows, int32_t cols, int32_t dtype, void* packed,
+                        void* stream);
+
 /* Expert FFN over the permuted buffer (Sec. 2.1: experts are parallel FFNs; each replica
  * processes the tokens dispatched to it).  Rows [slot_offsets[s], slot_offsets[s+1]) use
  * the weights of slot s:

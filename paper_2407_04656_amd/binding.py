@@ -13,7 +13,7 @@ __all__ = [
     "lz_route", "lz_plan_dispatch", "lz_permute", "lz_permute_scatter", "lz_expert_ffn", "lz_unpermute_combine",
     "lz_ffn_tiles", "lz_ffn_up", "lz_ffn_down", "lz_allocate_replicas", "lz_place_mro", "lz_place_spread", "lz_place_compact", "lz_recovery_probability",
     "lz_replan", "lz_apply_transfers", "MoELayer",
-    "lz_train_workspace_bytes", "lz_ffn_forward_train", "lz_combine_backward",
+    "lz_pack_weights", "lz_train_workspace_bytes", "lz_ffn_forward_train", "lz_combine_backward",
     "lz_ffn_backward", "lz_permute_backward", "lz_route_backward", "lz_reduce_replica_grads",
 ]
 
@@ -111,6 +111,7 @@ def _load():
         "lz_recovery_probability": (i32, [vp, i32, i32, i32, i32, vp, vp]),
         "lz_replan": (i32, [vp, i32, i32, vp, vp, i32, i32, i32, vp, vp, vp, vp, vp]),
         "lz_apply_transfers": (i32, [vp, i32, vp, vp, i32, vp, vp, i32, sp, vp]),
+        "lz_pack_weights": (i32, [vp, i32, i32, i32, i32, vp, vp]),
         "lz_train_workspace_bytes": (u64, [sp]),
         "lz_ffn_forward_train": (i32, [vp, vp, vp, vp, sp, vp, vp, vp, vp, u64, vp]),
         "lz_combine_backward": (i32, [vp, vp, vp, vp, sp, vp, vp, vp]),
@@ -186,6 +187,11 @@ def lz_permute(x, row_to_pair, shape, xp, stream=None):
 def lz_permute_scatter(x, pair_to_row, shape, xp, stream=None):
     _check(lib.lz_permute_scatter(_ptr(x), _ptr(pair_to_row), C.byref(shape.c_struct()), _ptr(xp),
                                   _stream() if stream is None else stream), "lz_permute_scatter")
+
+
+def lz_pack_weights(w, S, rows, cols, dtype, packed, stream=None):
+    _check(lib.lz_pack_weights(_ptr(w), S, rows, cols, dtype, _ptr(packed),
+                               _stream() if stream is None else stream), "lz_pack_weights")
 
 
 def lz_expert_ffn(xp, slot_offsets, w1, w2, shape, yp, ws, ws_bytes, stream=None):
@@ -371,8 +377,8 @@ class MoELayer:
 
     def load_expert_weights(self, w1_experts, w2_experts, slot_expert):
         """Give every slot its own copy of its expert's weights.  The host arrays are indexed by
-        expert and come in the usual [out, in] layout (w1 [E, n1, d], w2 [E, d, ffn]); the device
-        copies are their transposes."""
+        expert and come in the usual [out, in] layout (w1 [E, n1, d], w2 [E, d, ffn]); every expert
+        is converted once with lz_pack_weights and copied to its slots."""
         import torch
         s = self.shape
         tdt = torch.float32 if s.dtype == LZ_F32 else torch.bfloat16
@@ -381,7 +387,10 @@ class MoELayer:
             t = torch.from_numpy(a)
             if s.dtype == LZ_BF16:
                 t = t.view(torch.bfloat16)
-            return t.to(self.device).t().contiguous()
+            t = t.to(self.device)
+            packed = torch.empty((t.shape[1], t.shape[0]), dtype=t.dtype, device=self.device)
+            lz_pack_weights(t, 1, t.shape[0], t.shape[1], s.dtype, packed)
+            return packed
 
         n1 = w1_experts.shape[1]
         self.w1 = torch.empty((s.S, s.d, n1), dtype=tdt, device=self.device)

@@ -342,3 +342,26 @@ def test_padded_ep_reference_path_equals_flexible_dispatch():
     assert o["rank_rows_max"] <= 1.2 * o["rank_rows_mean"]           # flexible dispatch: ranks nearly level
     assert o["ep_rank_rows"] >= 1.3 * o["rank_rows_mean"]            # padded EP: everyone pays for the fullest slot
     assert o["ep_rows_total"] == N * c * o["ep_capacity"]
+
+
+@pytest.mark.parametrize("dtype,rows,cols", [("bf16", 100, 72), ("f32", 33, 65), ("bf16", 256, 512), ("f32", 1, 7)])
+def test_pack_weights_is_an_exact_transpose(dtype, rows, cols):
+    rng = np.random.default_rng(rows * 1000 + cols)
+    S = 3
+    host = rng.standard_normal((S, rows, cols)).astype(np.float32)
+    bf16 = dtype == "bf16"
+    if bf16:
+        host = f32_to_bf16_bits(host)
+    src = to_dev(host, bf16)
+    dst = torch.zeros((S, cols, rows), dtype=src.dtype, device=DEV)
+    lz.lz_pack_weights(src, S, rows, cols, lz.LZ_BF16 if bf16 else lz.LZ_F32, dst)
+    assert np.array_equal(to_host(dst), host.transpose(0, 2, 1))
+    back = torch.zeros_like(src)
+    lz.lz_pack_weights(dst, S, cols, rows, lz.LZ_BF16 if bf16 else lz.LZ_F32, back)      # its own inverse
+    assert np.array_equal(to_host(back), host)
+    with pytest.raises(lz.LzError) as e:
+        lz.lz_pack_weights(src, S, rows, cols, 7, dst)
+    assert e.value.code == -2
+    with pytest.raises(lz.LzError) as e:
+        lz.lz_pack_weights(src, S, rows, cols, lz.LZ_F32, src)
+    assert e.value.code == -1

@@ -161,3 +161,9 @@ def test_training_calls_validate_arguments_without_a_gpu():
     with pytest.raises(lz.LzError) as ei:
         lz.lz_permute_backward(None, None, ok, None, stream=0)
     assert ei.value.code == -1
+    with pytest.raises(lz.LzError) as ei:
+        lz.lz_pack_weights(None, 2, 64, 64, lz.LZ_BF16, None, stream=0)
+    assert ei.value.code == -1
+    with pytest.raises(lz.LzError) as ei:
+        lz.lz_pack_weights(None, 2, 0, 64, lz.LZ_BF16, None, stream=0)
+    assert ei.value.code == -2
