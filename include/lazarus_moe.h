@@ -207,9 +207,9 @@ int32_t lz_unpermute_combine(const void* yp, const int32_t* pair_to_row,
 size_t lz_train_workspace_bytes(const lz_shape* shape);
 
 /* lz_expert_ffn that also returns what the backward needs: z = xp W1 (pre-activation,
- * [P, n1]; SwiGLU: columns [0,ffn) gate, [ffn,2ffn) up) and h = act(z) [P, ffn].  The
- * activation is applied to the bf16-rounded z.  Rows of z and yp outside every slot are left
- * untouched, such rows of h are unspecified.
+ * [P, n1]; SwiGLU: columns [0,ffn) gate, [ffn,2ffn) up) and h = act(z) [P, ffn], both written
+ * by the first GEMM's epilogue.  The activation is applied to the bf16-rounded z.  Rows outside
+ * every slot are left untouched.
  *   xp dev [P,d], w1 dev [S,d,n1], w2 dev [S,ffn,d], z dev [P,n1] out, h dev [P,ffn] out, yp dev [P,d] out */
 int32_t lz_ffn_forward_train(const void* xp, const int32_t* slot_offsets, const void* w1, const void* w2,
                              const lz_shape* shape, void* z, void* h, void* yp, void* ws, size_t ws_bytes,

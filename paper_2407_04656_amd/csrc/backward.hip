@@ -142,29 +142,6 @@ __device__ __forceinline__ float gelu_grad_fast(float v) {
   return fmaf(v * 0.3989422804014327f, e, cdf);
 }
 
-// H = act(Z): Z [P, n1] -> H [P, ffn]
-template <bool SWIGLU>
-__global__ __launch_bounds__(256) void act_forward_kernel(const u32x4* __restrict__ Z, long long P, int ffn_vec,
-                                                          u32x4* __restrict__ H) {
-  const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
-  if (i >= P * ffn_vec) return;
-  const long long row = i / ffn_vec;
-  const int v = int(i % ffn_vec);
-  const int z_vec = SWIGLU ? 2 * ffn_vec : ffn_vec;
-  float a[8], o[8];
-  unpack8(__builtin_nontemporal_load(Z + row * z_vec + v), a);
-  if (SWIGLU) {
-    float u[8];
-    unpack8(__builtin_nontemporal_load(Z + row * z_vec + ffn_vec + v), u);
-#pragma unroll
-    for (int q = 0; q < 8; ++q) o[q] = silu_fast(a[q]) * u[q];
-  } else {
-#pragma unroll
-    for (int q = 0; q < 8; ++q) o[q] = gelu_fast(a[q]);
-  }
-  __builtin_nontemporal_store(pack8(o), H + i);
-}
-
 // dZ = dH * act'(Z)
 template <bool SWIGLU>
 __global__ __launch_bounds__(256) void act_backward_kernel(const u32x4* __restrict__ dH, const u32x4* __restrict__ Z,
@@ -231,7 +208,7 @@ struct TrainWorkspace {
   uint16_t* dz;        // [P, n1]
   int32_t* virt_w2;    // [S+1]
   int32_t* virt_w1;    // [S+1]
-  void* tiles_fwd;     // rows of the batch: lists for n1 / 256 and d / 256 column tiles
+  void* tiles_fwd;     // rows of the batch: lists for the forward's two GEMMs (ffn / 128 or 256, d / 256 column tiles)
   void* tiles_bwd;     // rows of the batch: lists for ffn / 256 and d / 256 column tiles
   void* tiles_w2;      // S * ffn virtual rows, d / 256 column tiles
   void* tiles_w1;      // S * d virtual rows, n1 / 256 column tiles
@@ -256,7 +233,7 @@ TrainWorkspace carve_train(void* ws, const lz_shape* s) {
   w.dz = (uint16_t*)take((size_t)P * w.n1 * 2);
   w.virt_w2 = (int32_t*)take(sizeof(int32_t) * (S + 1));
   w.virt_w1 = (int32_t*)take(sizeof(int32_t) * (S + 1));
-  w.tiles_fwd = take(tile_table_bytes(P, S, BM, kGroupM, ceil_div(w.n1, BN), s->d / BN));
+  w.tiles_fwd = take(tile_table_bytes(P, S, BM, kGroupM, ceil_div(s->ffn, s->act == LZ_SWIGLU ? BN / 2 : BN), s->d / BN));
   w.tiles_bwd = take(tile_table_bytes(P, S, BM, kGroupM, ceil_div(s->ffn, BN), s->d / BN));
   w.tiles_w2 = take(tile_table_bytes((long long)S * s->ffn, S, BM, kGroupM, s->d / BN, 0));
   w.tiles_w1 = take(tile_table_bytes((long long)S * s->d, S, BM, kGroupM, ceil_div(w.n1, BN), 0));
@@ -365,20 +342,28 @@ extern "C" int32_t lz_ffn_forward_train(const void* xp, const int32_t* slot_offs
     return LZ_EINVAL;
   hipStream_t st = (hipStream_t)stream;
   const int S = shape->N * shape->c;
+  const bool swiglu = shape->act == LZ_SWIGLU;
+  const int n_up = ceil_div(shape->ffn, swiglu ? BN / 2 : BN);
   TileTable t;
-  int32_t r = build_table(slot_offsets, S, P, ceil_div(w.n1, BN), shape->d / BN, w.tiles_fwd, st, &t);
+  int32_t r = build_table(slot_offsets, S, P, n_up, shape->d / BN, w.tiles_fwd, st, &t);
   if (r != LZ_OK) return r;
-  r = gemm_nn((const uint16_t*)xp, (const uint16_t*)w1, (uint16_t*)z, P, shape->d, w.n1, 0, t, st);
-  if (r != LZ_OK) return r;
-  const int ffn_vec = shape->ffn / 8;
-  const unsigned blocks = (unsigned)((P * ffn_vec + 255) / 256);
-  if (shape->act == LZ_SWIGLU)
-    hipLaunchKernelGGL(act_forward_kernel<true>, dim3(blocks), dim3(256), 0, st, (const u32x4*)z, P, ffn_vec,
-                       (u32x4*)h);
-  else
-    hipLaunchKernelGGL(act_forward_kernel<false>, dim3(blocks), dim3(256), 0, st, (const u32x4*)z, P, ffn_vec,
-                       (u32x4*)h);
-  r = lz::launch_status();
+  // z = xp W1 and h = act(z) from one epilogue
+  MfmaArgs g{};
+  g.A = (const uint16_t*)xp;
+  g.W = (const uint16_t*)w1;
+  g.C = (uint16_t*)h;
+  g.Z = (uint16_t*)z;
+  g.z_cols = w.n1;
+  g.P = P;
+  g.K = shape->d;
+  g.w_rows = w.n1;
+  g.n_out = shape->ffn;
+  g.up_row0 = swiglu ? shape->ffn : 0;
+  g.n_tiles = n_up;
+  g.which = 0;
+  g.t = t;
+  g.ldw = w.n1;
+  r = swiglu ? launch_mfma<EPI_SWIGLU_KEEP, MODE_NN>(g, st) : launch_mfma<EPI_GELU_KEEP, MODE_NN>(g, st);
   if (r != LZ_OK) return r;
   return gemm_nn((const uint16_t*)h, (const uint16_t*)w2, (uint16_t*)yp, P, shape->ffn, shape->d, 1, t, st);
 }

@@ -29,7 +29,8 @@ constexpr int kTileHeader = 64;  // ints before the tile arrays; [0] = number of
 constexpr int kGroupM = 4;       // row tiles of a work unit (same slot)
 constexpr int kGroupN = 8;       // column tiles of a work unit
 
-enum { EPI_NONE = 0, EPI_GELU = 1, EPI_SWIGLU = 2 };
+// *_KEEP: the training forward; besides act(z) the pre-activation z goes to MfmaArgs::Z
+enum { EPI_NONE = 0, EPI_GELU = 1, EPI_SWIGLU = 2, EPI_GELU_KEEP = 3, EPI_SWIGLU_KEEP = 4 };
 
 struct TileTable {
   int32_t* header;
@@ -180,6 +181,8 @@ struct MfmaArgs {
   // MODE_TN (weight gradients): slot s contracts over the rows [slot_offsets[s], slot_offsets[s+1])
   // of both operands and owns rows_per_slot rows of C (row index = s * rows_per_slot + m, m =
   // column of A).
+  uint16_t* Z;          // *_KEEP epilogues: pre-activations [P, z_cols] (SwiGLU: gate columns, then up columns)
+  int z_cols;
   int lda, ldw;         // row strides (elements) of the k-major operands
   const int32_t* slot_offsets;
   long long k_rows;
@@ -269,6 +272,7 @@ __device__ __forceinline__ void sched_slice() {
 template <int EPI, int XF, int MODE>
 __device__ __forceinline__ void gemm_tile(const MfmaArgs& a, char* smem, int slot, int row0, int row_end, int n0) {
   constexpr bool TA = MODE == MODE_TN, TB = MODE != MODE_NT;  // k-major left / right operand
+  constexpr bool kGated = EPI == EPI_SWIGLU || EPI == EPI_SWIGLU_KEEP;
   constexpr int KS = BK / 16;             // 16-wide MFMA slices per stage
   constexpr int kLoadsX = TA ? 8 : 2 * XF;  // 1-KiB wave loads per wave for the left tile (8 rows, or 2 k-rows, each)
   constexpr int kLoadsW = 8;              // ... for the 256-row weight tile
@@ -348,7 +352,7 @@ __device__ __forceinline__ void gemm_tile(const MfmaArgs& a, char* smem, int slo
   }
 #pragma unroll
   for (int i = 0; i < kLoadsW; ++i) {
-    if constexpr (TB && EPI == EPI_SWIGLU) {
+    if constexpr (TB && kGated) {
       // k-major SwiGLU weights [K, 2 ffn]: 32-column fragments alternate gate and up columns
       const int kr = (wave * 8 + i) * 2 + (lane >> 5);
       const int piece = (lane & 31) ^ ((kr & 3) << 2);
@@ -361,7 +365,7 @@ __device__ __forceinline__ void gemm_tile(const MfmaArgs& a, char* smem, int slo
       const int r = (wave * kLoadsW + i) * 8 + (lane >> 3);
       const int chunk = (lane & 7) ^ swz(r);
       int gb;
-      if (EPI == EPI_SWIGLU) {
+      if (kGated) {
         const int f = r >> 5;  // fragment index: even = gate rows, odd = up rows
         gb = n0 + (f >> 1) * 32 + (r & 31) + ((f & 1) ? a.up_row0 : 0);
       } else {
@@ -537,45 +541,26 @@ __device__ __forceinline__ void gemm_tile(const MfmaArgs& a, char* smem, int slo
   // second GEMM 10 % (timed with the stores removed).  So each 32-row fragment goes through a
   // per-wave LDS patch (the stages are dead by now; LDS serves a wave's accesses in order) and
   // leaves as 16 bytes per lane, whole 128-byte lines at a time.
-  constexpr int kWaveCols = EPI == EPI_SWIGLU ? 64 : 128;  // output columns of this wave
+  constexpr int kWaveCols = kGated ? 64 : 128;             // output columns of this wave
   constexpr int kPitch = kWaveCols * 2 + 16;               // patch row in bytes: 16-byte aligned, rows 4 banks apart
   constexpr int kLanesPerRow = kWaveCols / 8;              // 16-byte pieces of a patch row
   constexpr int kRowsPerStore = 64 / kLanesPerRow;
   char* const patch = smem + wave * (32 * kPitch);
   const int half = lane >> 5;
-#pragma unroll
-  for (int j = 0; j < XF; ++j) {
+  // One pass of fragment j through the patch: value(blk, v) is the number for patch column
+  // blk*32 + 8*(v/4) + 4*half + v%4; the patch then leaves for dst[row, col0 + ...], columns
+  // from col_end on are not stored.
+  auto pass = [&](int j, auto value, uint16_t* dst, int ld, int col0, int col_end) {
     char* const prow = patch + (lane & 31) * kPitch;
-    if (EPI == EPI_SWIGLU) {
 #pragma unroll
-      for (int q = 0; q < 2; ++q)
+    for (int blk = 0; blk < kWaveCols / 32; ++blk)
 #pragma unroll
-        for (int g = 0; g < 4; ++g) {
-          float o[4];
-#pragma unroll
-          for (int r = 0; r < 4; ++r) o[r] = silu_fast(acc[2 * q][j][4 * g + r]) * acc[2 * q + 1][j][4 * g + r];
-          uint2 pk;
-          pk.x = pack_bf16x2(o[0], o[1]);
-          pk.y = pack_bf16x2(o[2], o[3]);
-          *(uint2*)(prow + (q * 32 + 8 * g + 4 * half) * 2) = pk;
-        }
-    } else {
-#pragma unroll
-      for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int g = 0; g < 4; ++g) {
-          float o[4];
-#pragma unroll
-          for (int r = 0; r < 4; ++r) {
-            o[r] = acc[i][j][4 * g + r];
-            if (EPI == EPI_GELU) o[r] = gelu_fast(o[r]);
-          }
-          uint2 pk;
-          pk.x = pack_bf16x2(o[0], o[1]);
-          pk.y = pack_bf16x2(o[2], o[3]);
-          *(uint2*)(prow + (i * 32 + 8 * g + 4 * half) * 2) = pk;
-        }
-    }
+      for (int g = 0; g < 4; ++g) {
+        uint2 pk;
+        pk.x = pack_bf16x2(value(blk, 4 * g), value(blk, 4 * g + 1));
+        pk.y = pack_bf16x2(value(blk, 4 * g + 2), value(blk, 4 * g + 3));
+        *(uint2*)(prow + (blk * 32 + 8 * g + 4 * half) * 2) = pk;
+      }
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");  // keep the patch writes before the reads below
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
@@ -584,12 +569,34 @@ __device__ __forceinline__ void gemm_tile(const MfmaArgs& a, char* smem, int slo
       const int r = t * kRowsPerStore + lane / kLanesPerRow, piece = lane % kLanesPerRow;
       const uint4 v = *(const uint4*)(patch + r * kPitch + piece * 16);
       const int row = row0 + wm * 32 * XF + j * 32 + r;
-      const int col = n0 + wn * kWaveCols + piece * 8;  // n_out is a multiple of 8
-      if (row < row_end && col < a.n_out) *(uint4*)(a.C + (size_t)row * a.n_out + col) = v;
+      const int col = col0 + piece * 8;  // row lengths are multiples of 8
+      if (row < row_end && col < col_end) *(uint4*)(dst + (size_t)row * ld + col) = v;
     }
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");  // ... and the reads before the next fragment's writes
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");  // ... and the reads before the next pass's writes
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+  };
+  auto rounded = [](float v) { return __uint_as_float(pack_bf16x2(v, 0.f) << 16); };  // the bf16 value that is stored
+  const int out0 = n0 + wn * kWaveCols;
+#pragma unroll
+  for (int j = 0; j < XF; ++j) {
+    if constexpr (EPI == EPI_SWIGLU) {
+      pass(j, [&](int q, int v) { return silu_fast(acc[2 * q][j][v]) * acc[2 * q + 1][j][v]; }, a.C, a.n_out, out0,
+           a.n_out);
+    } else if constexpr (EPI == EPI_SWIGLU_KEEP) {
+      pass(j, [&](int q, int v) { return acc[2 * q][j][v]; }, a.Z, a.z_cols, out0, a.n_out);
+      pass(j, [&](int q, int v) { return acc[2 * q + 1][j][v]; }, a.Z, a.z_cols, a.up_row0 + out0,
+           a.up_row0 + a.n_out);
+      pass(j, [&](int q, int v) { return silu_fast(rounded(acc[2 * q][j][v])) * rounded(acc[2 * q + 1][j][v]); },
+           a.C, a.n_out, out0, a.n_out);
+    } else if constexpr (EPI == EPI_GELU_KEEP) {
+      pass(j, [&](int i, int v) { return acc[i][j][v]; }, a.Z, a.z_cols, out0, a.n_out);
+      pass(j, [&](int i, int v) { return gelu_fast(rounded(acc[i][j][v])); }, a.C, a.n_out, out0, a.n_out);
+    } else if constexpr (EPI == EPI_GELU) {
+      pass(j, [&](int i, int v) { return gelu_fast(acc[i][j][v]); }, a.C, a.n_out, out0, a.n_out);
+    } else {
+      pass(j, [&](int i, int v) { return acc[i][j][v]; }, a.C, a.n_out, out0, a.n_out);
+    }
   }
 }
 
@@ -608,7 +615,7 @@ template <int EPI, int MODE = MODE_NT>
 __global__ __launch_bounds__(256, 1) void gemm_mfma_kernel(MfmaArgs a) {
 #if defined(__HIP_DEVICE_COMPILE__)  // the host pass only needs the launch stub, not the gfx950 builtins
   extern __shared__ __attribute__((aligned(1024))) char smem[];
-  constexpr int BN_OUT = EPI == EPI_SWIGLU ? BN / 2 : BN;
+  constexpr int BN_OUT = (EPI == EPI_SWIGLU || EPI == EPI_SWIGLU_KEEP) ? BN / 2 : BN;
   constexpr int kUnitTiles = kGroupM * kGroupN;
   const int xcd = blockIdx.x % 8;  // workgroups are dealt round-robin to the 8 XCDs
   const int n_col_groups = (a.n_tiles + kGroupN - 1) / kGroupN;
