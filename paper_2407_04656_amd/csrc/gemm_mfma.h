@@ -266,8 +266,8 @@ __device__ __forceinline__ void sched_slice() {
   }
 }
 
-// One output tile of 64*XF rows x 256 weight rows.  XF = 32-row activation fragments per
-// wave: the 2x2 waves each own (32*XF) x 128 of the tile, so a slot's ragged last tile costs
+// One output tile of 64*XF rows x 256 columns n of the weight operand W(n, k) ("weight rows"
+// below, whichever way W lies in memory).  XF = 32-row activation fragments per wave: the 2x2 waves each own (32*XF) x 128 of the tile, so a slot's ragged last tile costs
 // MFMAs and activation loads only for its rows rounded up to 64.
 template <int EPI, int XF, int MODE>
 __device__ __forceinline__ void gemm_tile(const MfmaArgs& a, char* smem, int slot, int row0, int row_end, int n0) {
