@@ -131,7 +131,9 @@ def training_pass(torch, lz, layer, cfg, logits, x, iters=5):
     if lz.lz_train_workspace_bytes(s) == 0:
         return None
     layer.enable_training()
-    dy = torch.randn((s.T, s.d), device=layer.device).to(torch.bfloat16)
+    gen = torch.Generator(device=layer.device)
+    gen.manual_seed(1000 + cfg.seed)        # upstream gradient: seeded N(0, 1), rounded to bf16
+    dy = torch.randn((s.T, s.d), device=layer.device, generator=gen).to(torch.bfloat16)
     n1 = layer.w1.shape[2]
     P, S = s.P, s.S
 
