@@ -20,6 +20,8 @@ Every function names the passage it follows.  Where the paper is silent, garbled
 ambiguous the reading taken is stated in the docstring.  Pins (tests that tie each
 function to something other than itself) live in tests/test_oracle_*.py.
 
-Parity unpinned: the tie-breaking order of the greedy node mapping in
-`planner.replan` (the paper gives no worked example; only cost properties are pinned).
+Every function has a pin.  The order and tie rule of the greedy node mapping in
+`planner.replan` are a reading (the paper gives no worked example): the implementation of that
+reading is pinned by hand-worked cases (tests/golden/replan_handworked.txt) and by an
+arg-min check of every pick on random instances.
 """

@@ -532,7 +532,12 @@ __device__ __forceinline__ void gemm_tile(const MfmaArgs& a, char* smem, int slo
     mma(1);
     sched_slice<0, kDsReads, 4 * XF, kAfterBarrier>();
   }
-  __builtin_amdgcn_s_waitcnt(0x0F70);  // drain the (empty) trailing loads before LDS is reused
+  // The trailing loads (steps past the end of K, zero-length descriptor) still write zeros into
+  // stage `cur`, and each wave only waits for its own: with an odd number of K steps that is
+  // stage 0, where the epilogue patches of the other waves lie.  Drain this wave's, then wait
+  // until every wave has drained its own, before anybody writes a patch.
+  __builtin_amdgcn_s_waitcnt(0x0F70);
+  __syncthreads();
 
   // ---- epilogue.  acc[i][j] is the 32x32 block (weight fragment i) x (activation fragment j);
   // lane l holds activation row j*32 + l%32 and, for g = 0..3, the 4 consecutive weight rows

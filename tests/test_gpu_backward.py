@@ -283,6 +283,55 @@ def test_full_config_backward(name):
     assert np.allclose(to_host(layer.dlogits), dl_ref, rtol=1e-4, atol=1e-5 * np.max(np.abs(dl_ref)))
 
 
+def test_odd_number_of_k_steps_with_short_tail_tiles_is_reproducible():
+    """Regression: with an odd number of 64-wide K steps the trailing (empty) direct-to-LDS loads of
+    one wave land in the LDS stage that holds the other waves' epilogue patches; the kernel has to
+    wait for every wave's loads before the first patch is written.  ffn = 320 gives the data
+    gradient dxp = dZ W1^T five K steps, the slot sizes give the weight gradients 1, 3 and 5 K
+    steps, and the <= 64-row tail tiles run the narrowest tile variant.  Every repetition must
+    give the same bits, and those bits must match the oracle."""
+    cfg = scaled(CONFIGS["c1_tiny"], act="gelu", dtype="bf16", T=361, k=2, d=256, ffn=320, N=3, c=2)
+    counts = [60, 300, 33, 1, 64, 264]
+    S, P = 6, cfg.T * cfg.k
+    assert sum(counts) == P
+    offsets = np.zeros(S + 1, dtype=np.int32)
+    offsets[1:] = np.cumsum(counts)
+    rng = np.random.default_rng(17)
+    slot_expert = np.array([1, 0, 4, 7, 2, 5], dtype=np.int32)
+    w = expert_weights(cfg, threads=2)
+    xph, dyph = _bf16(rng, (P, cfg.d)), _bf16(rng, (P, cfg.d), 0.5)
+    shape = lz.Shape.from_config(cfg)
+    bf = torch.bfloat16
+    w1, w2 = slot_weights(w, slot_expert, True)
+    n = lz.lz_train_workspace_bytes(shape)
+    ws = torch.empty(n, dtype=torch.uint8, device=DEV)
+    xp, dyp, off = to_dev(xph, True), to_dev(dyph, True), to_dev(offsets)
+    first = None
+    for rep in range(6):
+        z = torch.zeros((P, cfg.ffn), dtype=bf, device=DEV)
+        h = torch.zeros((P, cfg.ffn), dtype=bf, device=DEV)
+        yp = torch.zeros((P, cfg.d), dtype=bf, device=DEV)
+        dxp = torch.zeros((P, cfg.d), dtype=bf, device=DEV)
+        dw1 = torch.zeros((S, cfg.d, cfg.ffn), dtype=bf, device=DEV)
+        dw2 = torch.zeros((S, cfg.ffn, cfg.d), dtype=bf, device=DEV)
+        lz.lz_ffn_forward_train(xp, off, w1, w2, shape, z, h, yp, ws, n)
+        lz.lz_ffn_backward(dyp, xp, z, h, off, w1, w2, shape, dxp, dw1, dw2, ws, n)
+        torch.cuda.synchronize()
+        outs = [t.view(torch.int16).clone() for t in (yp, dxp, dw1, dw2)]
+        if first is None:
+            first = outs
+        else:
+            for a_, b_ in zip(first, outs):
+                assert torch.equal(a_, b_), rep
+    dxp_ref, dw1_ref, dw2_ref = ob.ffn_backward_rows(dyph, xph, offsets, slot_expert, w["w1"], w["w2"], cfg.act)
+    assert rel_err(first[1].view(torch.uint16).cpu().numpy(), dxp_ref) <= TOL
+    assert rel_err(first[2].view(torch.uint16).cpu().numpy(), dw1_ref.transpose(0, 2, 1)) <= TOL
+    assert rel_err(first[3].view(torch.uint16).cpu().numpy(), dw2_ref.transpose(0, 2, 1)) <= TOL
+    # row by row: a zeroed output row would hide behind the tensor's maximum
+    got = om.widen(first[1].view(torch.uint16).cpu().numpy())
+    assert np.all(np.max(np.abs(got - dxp_ref), axis=1) <= TOL * np.max(np.abs(dxp_ref), axis=1) * 2 + 1e-6)
+
+
 def test_backward_without_tokens_and_with_bad_offsets():
     """T = 0: every call succeeds and the weight gradients are exact zeros.  Offsets outside
     [0, P] or decreasing are clipped as in the forward: never an out-of-bounds access, and the

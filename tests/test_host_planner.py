@@ -108,6 +108,19 @@ def test_replan_matches_oracle():
     assert ok > 100 and unrec > 10
 
 
+def test_replan_handworked_cases_through_the_library(golden_dir):
+    """The hand-worked Sec. 4.3 cases (tests/golden/replan_handworked.txt) through lz_replan."""
+    from test_oracle_planner import load_replan_cases
+    cases = load_replan_cases(golden_dir)
+    assert len(cases) >= 6
+    for cs in cases:
+        got = lz.lz_replan(cs["old"], cs["N_old"], cs["c_old"], np.array(cs["alive"], dtype=np.uint8),
+                           np.array(cs["t"]), cs["c_new"], 1)
+        assert got["plan2phys"].tolist() == cs["plan2phys"], cs["name"]
+        assert got["new_slot_expert"].tolist() == cs["new"], cs["name"]
+        assert [tuple(x) for x in got["transfers"]] == cs["transfers"], cs["name"]
+
+
 def test_device_calls_validate_arguments_without_a_gpu():
     bad = lz.Shape(T=16, d=8, ffn=8, E=4, k=9, N=2, c=2, dtype=lz.LZ_F32, act=lz.LZ_GELU)
     assert lz.lz_plan_workspace_bytes(bad) == 0 and lz.lz_ffn_workspace_bytes(bad) == 0

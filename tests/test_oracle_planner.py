@@ -278,17 +278,51 @@ def test_replan_properties():
             owners = [p for p in survivors if e in old[p * c:(p + 1) * c]]
             counts = [len(per_owner.get(p, ())) for p in owners]
             assert max(counts) - min(counts) <= 1
-        # greedy mapping never costs more than leaving the plan nodes in their given order
+        # greedy mapping: every survivor, in ascending id, holds the arg-min (lowest plan node on
+        # ties) of the newly assigned experts among the plan nodes not taken by an earlier survivor
         held = {p: set(old[p * c:(p + 1) * c]) for p in survivors}
-        cost = sum(len(set(out["plan"][q * c_new:(q + 1) * c_new]) - held[p])
-                   for q, p in enumerate(out["plan2phys"]))
+        plan_sets = [set(out["plan"][q * c_new:(q + 1) * c_new]) for q in range(Nn)]
+        unused = list(range(Nn))
+        for p in survivors:
+            costs = [len(plan_sets[q] - held[p]) for q in unused]
+            want = unused[costs.index(min(costs))]
+            assert out["plan2phys"][want] == p, (trial, p, want)
+            unused.remove(want)
         done += 1
-        first = survivors[0]
-        best_first = min(len(set(out["plan"][q * c_new:(q + 1) * c_new]) - held[first]) for q in range(Nn))
-        q_first = out["plan2phys"].index(first)
-        assert len(set(out["plan"][q_first * c_new:(q_first + 1) * c_new]) - held[first]) == best_first
-        assert cost >= 0
     assert done > 50
+
+
+def load_replan_cases(golden_dir):
+    """tests/golden/replan_handworked.txt -> list of dicts (all values plain Python ints)."""
+    cases = []
+    with open(os.path.join(golden_dir, "replan_handworked.txt")) as fh:
+        for line in fh:
+            line = line.strip()
+            if not line or line.startswith("#"):
+                continue
+            name, c_old, old, alive, t, c_new, plan, p2p, new, xf = [v.strip() for v in line.split("|")]
+            ranks = [_ints(r) for r in old.split("/")]
+            assert all(len(r) == int(c_old) for r in ranks)
+            cases.append({
+                "name": name, "c_old": int(c_old), "N_old": len(ranks), "old": [e for r in ranks for e in r],
+                "alive": _ints(alive), "t": _ints(t), "c_new": int(c_new),
+                "plan": [e for r in plan.split("/") for e in _ints(r)], "plan2phys": _ints(p2p),
+                "new": _ints(new), "transfers": [tuple(int(v) for v in tok.split(":")) for tok in xf.split()]})
+    return cases
+
+
+def test_replan_handworked(golden_dir):
+    """Sec. 4.3 worked by hand (Eq. 1 -> MRO -> greedy mapping -> transfers): ties on the first and
+    on a later pick, unique minima that are not the lowest node, a contested node going to the
+    lower rank, local extra replicas, fetches dealt round-robin, one fetch per (rank, expert)."""
+    cases = load_replan_cases(golden_dir)
+    assert len(cases) >= 6
+    for cs in cases:
+        out = op.replan(cs["old"], cs["N_old"], cs["c_old"], cs["alive"], cs["t"], cs["c_new"], 1)
+        assert out["plan"] == cs["plan"], cs["name"]
+        assert out["plan2phys"] == cs["plan2phys"], cs["name"]
+        assert out["new_slot_expert"] == cs["new"], cs["name"]
+        assert [tuple(x) for x in out["transfers"]] == cs["transfers"], cs["name"]
 
 
 def test_replan_no_change_needs_no_remote_transfer():
