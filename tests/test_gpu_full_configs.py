@@ -104,8 +104,9 @@ def test_activations_beyond_4gib():
 
 
 def test_post_failure_replan():
-    """Config 5: config 3's step-0 plan loses ranks 2 and 5; re-plan on 6 ranks x 8 slots, move the
-    weights with the transfer list, and run the layer under the new plan."""
+    """Config 5: config 3's step-0 plan loses ranks 6 and 7 (the config's drop_ranks); re-plan on
+    6 ranks x 8 slots, move the weights with the transfer list, and run the layer under the new plan.
+    The traffic keeps config 3's step-0 popularity ranking, the one the re-plan was proportioned for."""
     cfg = CONFIGS["c5_postfailure"]
     base = CONFIGS[cfg.base]
     w = expert_weights(base, threads=16)            # the model's weights are those of the base config

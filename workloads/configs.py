@@ -23,6 +23,7 @@ class LayerConfig:
     act: str              # "gelu" | "swiglu"
     seed: int
     steps: int = 1
+    ranking_seed: Optional[int] = None  # seed of the expert popularity ranking if not `seed`
     bias: str = "zipf"    # "normal": b ~ N(0, bias_param); "zipf": b = -s ln(rank+1)
     bias_param: float = 1.0
     reshuffle_every: int = 0          # redraw the popularity ranking every n steps (0 = never)
@@ -63,7 +64,10 @@ CONFIGS = {
     "c5_postfailure": LayerConfig(
         name="c5_postfailure", T=16384, d=2048, ffn=8192, E=32, k=2, N=6, c=8,
         dtype="bf16", act="gelu", seed=5, steps=100, bias="zipf", bias_param=1.2,
-        s_range=(0.8, 1.5), base="c3_gptmoe", base_N=8, base_c=6, drop_ranks=(6, 7)),
+        s_range=(0.8, 1.5), base="c3_gptmoe", base_N=8, base_c=6, drop_ranks=(6, 7),
+        # the traffic keeps the popularity ranking the re-plan was proportioned for: the base
+        # config's ranking at step 0 (its seed, epoch 0); only the Zipf exponent changes per step
+        ranking_seed=3),
 }
 
 ORDER = ["c1_tiny", "c2_mixtral", "c3_gptmoe", "c4_finegrained", "c5_postfailure"]

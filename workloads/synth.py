@@ -58,13 +58,16 @@ def popularity_bias(cfg: LayerConfig, step: int = 0) -> np.ndarray:
 
     "normal": b ~ N(0, bias_param) drawn once.  "zipf": a seeded ranking pi of the
     experts and b[e] = -s*ln(pi(e)+1), so softmax(b) is the Zipf(s) pmf over the
-    ranking; the ranking is redrawn every `reshuffle_every` steps when that is set.
+    ranking; the ranking is redrawn every `reshuffle_every` steps when that is set, and is
+    drawn from `ranking_seed` instead of `seed` when that is set (a post-failure workload
+    keeps the ranking of the configuration it re-plans).
     """
     if cfg.bias == "normal":
         return (_rng(cfg.seed, _STREAM_BIAS).standard_normal(cfg.E, dtype=np.float32)
                 * np.float32(cfg.bias_param)).astype(np.float32)
     epoch = step // cfg.reshuffle_every if cfg.reshuffle_every else 0
-    pi = _rng(cfg.seed, _STREAM_PERM, epoch).permutation(cfg.E)
+    perm_seed = cfg.seed if cfg.ranking_seed is None else cfg.ranking_seed
+    pi = _rng(perm_seed, _STREAM_PERM, epoch).permutation(cfg.E)
     s = zipf_exponent(cfg, step)
     return (-s * np.log(pi.astype(np.float64) + 1.0)).astype(np.float32)
 
