@@ -119,6 +119,24 @@ int32_t lz_plan_dispatch(const int32_t* topk_ids, const lz_shape* shape,
                          int32_t* Tej_opt, int32_t* D_opt, int32_t* status_opt,
                          void* ws, size_t ws_bytes, void* stream);
 
+/* lz_plan_dispatch for callers that cannot allocate or carry a workspace (code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc): same arguments minus the
+ * workspace, same kernels, same results.  The tables live in a fixed array of
+ * LZ_PLAN_NOALLOC_SCRATCH_BYTES of device memory inside the library (every GPU the library runs
+ * on holds its own copy until the process ends; its address is looked up once per GPU, on the
+ * first call there).  The call allocates nothing and frees nothing.
+ * LZ_EWORKSPACE if lz_plan_workspace_bytes(shape) exceeds LZ_PLAN_NOALLOC_SCRATCH_BYTES (all five
+ * benchmark configurations need less than 1 MiB).  All calls on one GPU share that GPU's array:
+ * calls that overlap in time on one GPU (two streams, two threads) race; order them.  Nothing in
+ * the array has to be cleared between calls. */
+#define LZ_PLAN_NOALLOC_SCRATCH_BYTES (4u << 20)
+int32_t lz_plan_dispatch_noalloc(const int32_t* topk_ids, const lz_shape* shape,
+                                 const int32_t* rank_tok_off, const int32_t* slot_expert,
+                                 int32_t* slot_counts, int32_t* slot_offsets,
+                                 int32_t* pair_to_row, int32_t* row_to_pair,
+                                 int32_t* Tej_opt, int32_t* D_opt, int32_t* status_opt,
+                                 void* stream);
+
 /* Reshuffle into per-slot contiguous buffers (Algorithm 1's h -> h'):
  * xp[row,:] = x[row_to_pair[row] / k, :]; rows whose map entry is outside [0,P) are
  * zero-filled.  x dev [T,d], xp dev [P,d], both of shape->dtype. */

@@ -10,7 +10,7 @@ import numpy as np
 __all__ = [
     "LZ_F32", "LZ_BF16", "LZ_GELU", "LZ_SWIGLU", "LzError", "Shape", "lib", "lib_path",
     "lz_strerror", "lz_version", "lz_plan_workspace_bytes", "lz_ffn_workspace_bytes",
-    "lz_route", "lz_plan_dispatch", "lz_permute", "lz_permute_scatter", "lz_expert_ffn", "lz_unpermute_combine",
+    "lz_route", "lz_plan_dispatch", "lz_plan_dispatch_noalloc", "LZ_PLAN_NOALLOC_SCRATCH_BYTES", "lz_permute", "lz_permute_scatter", "lz_expert_ffn", "lz_unpermute_combine",
     "lz_ffn_tiles", "lz_ffn_up", "lz_ffn_down", "lz_allocate_replicas", "lz_place_mro", "lz_place_spread", "lz_place_compact", "lz_recovery_probability",
     "lz_replan", "lz_apply_transfers", "MoELayer",
     "lz_pack_weights", "lz_train_workspace_bytes", "lz_ffn_forward_train", "lz_combine_backward",
@@ -19,6 +19,7 @@ __all__ = [
 
 LZ_F32, LZ_BF16 = 0, 1
 LZ_GELU, LZ_SWIGLU = 0, 1
+LZ_PLAN_NOALLOC_SCRATCH_BYTES = 4 << 20
 LZ_OK, LZ_EINVAL, LZ_ESHAPE, LZ_EWORKSPACE, LZ_EUNRECOVERABLE, LZ_EINFEASIBLE, LZ_EHIP = 0, -1, -2, -3, -4, -5, -6
 
 
@@ -97,6 +98,7 @@ def _load():
         "lz_ffn_workspace_bytes": (u64, [sp]),
         "lz_route": (i32, [vp, i32, i32, i32, vp, vp, vp]),
         "lz_plan_dispatch": (i32, [vp, sp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, u64, vp]),
+        "lz_plan_dispatch_noalloc": (i32, [vp, sp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]),
         "lz_permute": (i32, [vp, vp, sp, vp, vp]),
         "lz_permute_scatter": (i32, [vp, vp, sp, vp, vp]),
         "lz_expert_ffn": (i32, [vp, vp, vp, vp, sp, vp, vp, u64, vp]),
@@ -177,6 +179,15 @@ def lz_plan_dispatch(topk_ids, shape, rank_tok_off, slot_expert, slot_counts, sl
                                 _ptr(pair_to_row), _ptr(row_to_pair), _ptr(Tej_opt), _ptr(D_opt),
                                 _ptr(status_opt), _ptr(ws), ws_bytes,
                                 _stream() if stream is None else stream), "lz_plan_dispatch")
+
+
+def lz_plan_dispatch_noalloc(topk_ids, shape, rank_tok_off, slot_expert, slot_counts, slot_offsets, pair_to_row,
+                             row_to_pair, Tej_opt, D_opt, status_opt, stream=None):
+    _check(lib.lz_plan_dispatch_noalloc(_ptr(topk_ids), C.byref(shape.c_struct()), _ptr(rank_tok_off),
+                                        _ptr(slot_expert), _ptr(slot_counts), _ptr(slot_offsets),
+                                        _ptr(pair_to_row), _ptr(row_to_pair), _ptr(Tej_opt), _ptr(D_opt),
+                                        _ptr(status_opt), _stream() if stream is None else stream),
+           "lz_plan_dispatch_noalloc")
 
 
 def lz_permute(x, row_to_pair, shape, xp, stream=None):

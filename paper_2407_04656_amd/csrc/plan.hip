@@ -10,6 +10,8 @@
 //   place    each wave revisits its chunk; a pair's position in its (expert, source rank)
 //            list is chunk base + ordered rank inside the chunk (wave ballots, one per
 //            distinct expert), which fixes destination rank, slot and row
+#include <mutex>
+
 #include "lz_common.h"
 
 namespace {
@@ -399,18 +401,14 @@ extern "C" size_t lz_plan_workspace_bytes(const lz_shape* shape) {
   return carve(nullptr, shape).total_bytes;
 }
 
-extern "C" int32_t lz_plan_dispatch(const int32_t* topk_ids, const lz_shape* shape,
-                                    const int32_t* rank_tok_off, const int32_t* slot_expert,
-                                    int32_t* slot_counts, int32_t* slot_offsets, int32_t* pair_to_row,
-                                    int32_t* row_to_pair, int32_t* Tej_opt, int32_t* D_opt,
-                                    int32_t* status_opt, void* ws, size_t ws_bytes, void* stream) {
-  if (!lz::shape_ok(shape)) return LZ_ESHAPE;
-  if (!rank_tok_off || !slot_expert || !slot_counts || !slot_offsets) return LZ_EINVAL;
+namespace {
+
+// The four launches of the dispatcher on tables carved from `ws` (already checked by the caller).
+int32_t enqueue_plan(const int32_t* topk_ids, const lz_shape* shape, const int32_t* rank_tok_off,
+                     const int32_t* slot_expert, int32_t* slot_counts, int32_t* slot_offsets,
+                     int32_t* pair_to_row, int32_t* row_to_pair, int32_t* Tej_opt, int32_t* D_opt,
+                     int32_t* status_opt, const PlanTables& t, hipStream_t st) {
   const long long P = (long long)shape->T * shape->k;
-  if (P > 0 && (!topk_ids || !pair_to_row || !row_to_pair)) return LZ_EINVAL;
-  PlanTables t = carve(ws, shape);
-  if (!ws || (uintptr_t)ws % 256 != 0 || ws_bytes < t.total_bytes) return LZ_EWORKSPACE;
-  hipStream_t st = (hipStream_t)stream;
   const int nch = max_chunks(P, shape->N);
   const unsigned blocks = unsigned((nch + kWavesPerBlock - 1) / kWavesPerBlock);
   if (P > 0)
@@ -426,4 +424,78 @@ extern "C" int32_t lz_plan_dispatch(const int32_t* topk_ids, const lz_shape* sha
                        shape->E, shape->N, shape->c, shape->k, t, slot_offsets, pair_to_row,
                        row_to_pair);
   return lz::launch_status();
+}
+
+int32_t check_plan_args(const int32_t* topk_ids, const lz_shape* shape, const int32_t* rank_tok_off,
+                        const int32_t* slot_expert, const int32_t* slot_counts, const int32_t* slot_offsets,
+                        const int32_t* pair_to_row, const int32_t* row_to_pair) {
+  if (!lz::shape_ok(shape)) return LZ_ESHAPE;
+  if (!rank_tok_off || !slot_expert || !slot_counts || !slot_offsets) return LZ_EINVAL;
+  const long long P = (long long)shape->T * shape->k;
+  if (P > 0 && (!topk_ids || !pair_to_row || !row_to_pair)) return LZ_EINVAL;
+  return LZ_OK;
+}
+
+}  // namespace
+
+extern "C" int32_t lz_plan_dispatch(const int32_t* topk_ids, const lz_shape* shape,
+                                    const int32_t* rank_tok_off, const int32_t* slot_expert,
+                                    int32_t* slot_counts, int32_t* slot_offsets, int32_t* pair_to_row,
+                                    int32_t* row_to_pair, int32_t* Tej_opt, int32_t* D_opt,
+                                    int32_t* status_opt, void* ws, size_t ws_bytes, void* stream) {
+  const int32_t rc = check_plan_args(topk_ids, shape, rank_tok_off, slot_expert, slot_counts, slot_offsets,
+                                     pair_to_row, row_to_pair);
+  if (rc != LZ_OK) return rc;
+  PlanTables t = carve(ws, shape);
+  if (!ws || (uintptr_t)ws % 256 != 0 || ws_bytes < t.total_bytes) return LZ_EWORKSPACE;
+  return enqueue_plan(topk_ids, shape, rank_tok_off, slot_expert, slot_counts, slot_offsets, pair_to_row,
+                      row_to_pair, Tej_opt, D_opt, status_opt, t, (hipStream_t)stream);
+}
+
+// ------------------------------------------------------------------------------------------
+// The same dispatcher for callers that cannot allocate: its tables live in a fixed array in
+// device memory that belongs to the library (one copy per GPU, held until the process ends).
+// ------------------------------------------------------------------------------------------
+static __device__ __align__(256) unsigned char scratch[LZ_PLAN_NOALLOC_SCRATCH_BYTES];
+
+namespace {
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};  // device address of `scratch` on each GPU, looked up once
+
+// Address of this GPU's copy of `scratch`.  In host code the array's name is only a handle for
+// the runtime's symbol lookup, never a device address; every GPU has its own copy at its own address.
+int32_t scratch_of_current_device(void** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return LZ_EHIP;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return LZ_EHIP;
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return LZ_OK;
+}
+
+}  // namespace
+
+extern "C" int32_t lz_plan_dispatch_noalloc(const int32_t* topk_ids, const lz_shape* shape,
+                                            const int32_t* rank_tok_off, const int32_t* slot_expert,
+                                            int32_t* slot_counts, int32_t* slot_offsets,
+                                            int32_t* pair_to_row, int32_t* row_to_pair, int32_t* Tej_opt,
+                                            int32_t* D_opt, int32_t* status_opt, void* stream) {
+  const int32_t rc = check_plan_args(topk_ids, shape, rank_tok_off, slot_expert, slot_counts, slot_offsets,
+                                     pair_to_row, row_to_pair);
+  if (rc != LZ_OK) return rc;
+  if (carve(nullptr, shape).total_bytes > (size_t)LZ_PLAN_NOALLOC_SCRATCH_BYTES) return LZ_EWORKSPACE;
+  void* base = nullptr;
+  const int32_t rs = scratch_of_current_device(&base);
+  if (rs != LZ_OK) return rs;
+  // Every table entry a kernel reads was written earlier in the same call, so what the previous
+  // call left in the array does not matter and nothing has to be cleared.
+  const PlanTables t = carve(base, shape);
+  return enqueue_plan(topk_ids, shape, rank_tok_off, slot_expert, slot_counts, slot_offsets, pair_to_row,
+                      row_to_pair, Tej_opt, D_opt, status_opt, t, (hipStream_t)stream);
 }
