@@ -195,6 +195,20 @@ int32_t lz_ffn_up(const void* xp, const void* w1, const lz_shape* shape, void* w
 int32_t lz_ffn_down(const void* w2, const lz_shape* shape, void* yp, void* ws, size_t ws_bytes,
                     void* stream);
 
+/* The reshuffle fused into the first GEMM (Algorithm 1's h -> h' done by the consumer: the GEMM's
+ * activation loads read x through the row map, so no permuted copy of x is written or read):
+ *   lz_ffn_up_gather      hidden = act(x[row_to_pair[row] / k] W1) per slot   (replaces lz_permute + lz_ffn_up)
+ *   lz_expert_ffn_gather  tiles -> up_gather -> down                           (replaces lz_permute + lz_expert_ffn)
+ * Same results, bit for bit, as the unfused calls on the same inputs.  A row whose map entry is
+ * outside [0,P) reads as zeros (no such row lies inside a slot).  x dev [T,d] of shape->dtype,
+ * row_to_pair dev [P] i32 from lz_plan_dispatch; the other arguments as in lz_ffn_up / lz_expert_ffn.
+ * The MFMA path addresses x with 32-bit byte offsets: LZ_ESHAPE if T*d*2 >= 2^32 there. */
+int32_t lz_ffn_up_gather(const void* x, const int32_t* row_to_pair, const void* w1, const lz_shape* shape,
+                         void* ws, size_t ws_bytes, void* stream);
+int32_t lz_expert_ffn_gather(const void* x, const int32_t* row_to_pair, const int32_t* slot_offsets,
+                             const void* w1, const void* w2, const lz_shape* shape,
+                             void* yp, void* ws, size_t ws_bytes, void* stream);
+
 /* Inverse permutation and gate-weighted combine (Sec. 2.1, the second all-to-all and the
  * combine): y[t,:] = sum_{kk<k} topk_gates[t,kk] * yp[pair_to_row[t*k+kk], :], summed in
  * fp32 in ascending kk and rounded once; a pair whose row is outside [0,P) contributes 0.

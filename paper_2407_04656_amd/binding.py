@@ -11,7 +11,7 @@ __all__ = [
     "LZ_F32", "LZ_BF16", "LZ_GELU", "LZ_SWIGLU", "LzError", "Shape", "lib", "lib_path",
     "lz_strerror", "lz_version", "lz_plan_workspace_bytes", "lz_ffn_workspace_bytes",
     "lz_route", "lz_plan_dispatch", "lz_plan_dispatch_noalloc", "LZ_PLAN_NOALLOC_SCRATCH_BYTES", "lz_permute", "lz_permute_scatter", "lz_expert_ffn", "lz_unpermute_combine",
-    "lz_ffn_tiles", "lz_ffn_up", "lz_ffn_down", "lz_allocate_replicas", "lz_place_mro", "lz_place_spread", "lz_place_compact", "lz_recovery_probability",
+    "lz_ffn_tiles", "lz_ffn_up", "lz_ffn_down", "lz_ffn_up_gather", "lz_expert_ffn_gather", "lz_allocate_replicas", "lz_place_mro", "lz_place_spread", "lz_place_compact", "lz_recovery_probability",
     "lz_replan", "lz_apply_transfers", "MoELayer",
     "lz_pack_weights", "lz_train_workspace_bytes", "lz_ffn_forward_train", "lz_combine_backward",
     "lz_ffn_backward", "lz_permute_backward", "lz_route_backward", "lz_reduce_replica_grads",
@@ -106,6 +106,8 @@ def _load():
         "lz_ffn_tiles": (i32, [vp, sp, vp, u64, vp]),
         "lz_ffn_up": (i32, [vp, vp, sp, vp, u64, vp]),
         "lz_ffn_down": (i32, [vp, sp, vp, vp, u64, vp]),
+        "lz_ffn_up_gather": (i32, [vp, vp, vp, sp, vp, u64, vp]),
+        "lz_expert_ffn_gather": (i32, [vp, vp, vp, vp, vp, sp, vp, vp, u64, vp]),
         "lz_allocate_replicas": (i32, [vp, i32, i32, i32, i32, vp]),
         "lz_place_mro": (i32, [vp, vp, i32, i32, i32, vp]),
         "lz_place_spread": (i32, [vp, i32, i32, i32, vp]),
@@ -219,6 +221,17 @@ def lz_ffn_tiles(slot_offsets, shape, ws, ws_bytes, stream=None):
 def lz_ffn_up(xp, w1, shape, ws, ws_bytes, stream=None):
     _check(lib.lz_ffn_up(_ptr(xp), _ptr(w1), C.byref(shape.c_struct()), _ptr(ws), ws_bytes,
                          _stream() if stream is None else stream), "lz_ffn_up")
+
+
+def lz_ffn_up_gather(x, row_to_pair, w1, shape, ws, ws_bytes, stream=None):
+    _check(lib.lz_ffn_up_gather(_ptr(x), _ptr(row_to_pair), _ptr(w1), C.byref(shape.c_struct()), _ptr(ws), ws_bytes,
+                                _stream() if stream is None else stream), "lz_ffn_up_gather")
+
+
+def lz_expert_ffn_gather(x, row_to_pair, slot_offsets, w1, w2, shape, yp, ws, ws_bytes, stream=None):
+    _check(lib.lz_expert_ffn_gather(_ptr(x), _ptr(row_to_pair), _ptr(slot_offsets), _ptr(w1), _ptr(w2),
+                                    C.byref(shape.c_struct()), _ptr(yp), _ptr(ws), ws_bytes,
+                                    _stream() if stream is None else stream), "lz_expert_ffn_gather")
 
 
 def lz_ffn_down(w2, shape, yp, ws, ws_bytes, stream=None):
@@ -464,6 +477,15 @@ class MoELayer:
         self.dw2_slot = torch.empty((s.S, s.ffn, s.d), dtype=bf, device=dev)
         self.dw1 = torch.empty((s.E, s.d, n1), dtype=bf, device=dev)
         self.dw2 = torch.empty((s.E, s.ffn, s.d), dtype=bf, device=dev)
+
+    def forward_fused(self, logits, x):
+        """The same pass with the reshuffle done by the first GEMM's loads (no permute call, xp unused)."""
+        self.route(logits)
+        self.plan_dispatch()
+        lz_expert_ffn_gather(x, self.row_to_pair, self.slot_offsets, self.w1, self.w2, self.shape, self.yp,
+                             self.ffn_ws, self.ffn_ws_bytes)
+        self.unpermute_combine()
+        return self.y
 
     def forward_train(self, logits, x):
         self.route(logits)

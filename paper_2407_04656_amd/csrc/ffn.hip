@@ -37,11 +37,15 @@ __device__ __forceinline__ void store_elem<float>(float* p, float v) { *p = v; }
 template <>
 __device__ __forceinline__ void store_elem<uint16_t>(uint16_t* p, float v) { *p = lz::f32_to_bf16(v); }
 
-// C[rows of the tile, n] = epi( sum_k A[row, k] * W[slot][k, n (+ up_col0)] ),  W[slot] = [K, ldw]
+// C[rows of the tile, n] = epi( sum_k A[row, k] * W[slot][k, n (+ up_col0)] ),  W[slot] = [K, ldw].
+// With a row map (gather != nullptr) row r of the left operand is row gather[r] / gather_k of A,
+// zero if the map holds no pair for it.
 template <typename Elem, int EPI>
 __global__ __launch_bounds__(256) void gemm_generic_kernel(const Elem* __restrict__ A, int K,
                                                            const Elem* __restrict__ W, int ldw, int n_out,
-                                                           int up_col0, Elem* __restrict__ C, TileTable t) {
+                                                           int up_col0, Elem* __restrict__ C, TileTable t,
+                                                           const int32_t* __restrict__ gather, int gather_k,
+                                                           long long gather_T) {
   constexpr int BM = 64, BN = 64, BK = 16;
   constexpr bool DUAL = EPI == EPI_SWIGLU;
   __shared__ float sA[BK][BM + 1];
@@ -58,7 +62,14 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(const Elem* __restric
     for (int i = threadIdx.x; i < BM * BK; i += 256) {
       const int r = i / BK, kk = i % BK;
       const int row = row0 + r;
-      sA[kk][r] = (row < row_end && k0 + kk < K) ? load_elem<Elem>(A + (size_t)row * K + k0 + kk) : 0.f;
+      long long src = row;
+      bool ok = row < row_end && k0 + kk < K;
+      if (gather && ok) {
+        const long long pair = gather[row];
+        ok = pair >= 0 && pair < gather_T * gather_k;
+        src = ok ? pair / gather_k : 0;
+      }
+      sA[kk][r] = ok ? load_elem<Elem>(A + (size_t)src * K + k0 + kk) : 0.f;
     }
     for (int i = threadIdx.x; i < BN * BK; i += 256) {
       const int c = i % BN, kk = i / BN;  // consecutive threads read consecutive columns of a weight row
@@ -171,8 +182,11 @@ extern "C" int32_t lz_ffn_tiles(const int32_t* slot_offsets, const lz_shape* sha
   return lz::launch_status();
 }
 
-extern "C" int32_t lz_ffn_up(const void* xp, const void* w1, const lz_shape* shape, void* ws,
-                             size_t ws_bytes, void* stream) {
+namespace {
+
+// hidden = act(A W1) per slot; A = xp, or x read through the row map when `gather` is given
+int32_t ffn_up(const void* xp, const int32_t* gather, const void* w1, const lz_shape* shape, void* ws,
+               size_t ws_bytes, void* stream) {
   FfnWorkspace w;
   const int32_t rc = check_ffn(shape, ws, ws_bytes, &w);
   if (rc != LZ_OK) return rc;
@@ -183,28 +197,33 @@ extern "C" int32_t lz_ffn_up(const void* xp, const void* w1, const lz_shape* sha
   TileTable t = tiles_of(w, shape);
   const bool swiglu = shape->act == LZ_SWIGLU;
   const int n1 = shape->ffn * (swiglu ? 2 : 1);
+  const int gk = shape->k;
+  const long long gT = shape->T;
   if (!mfma_shape(shape)) {
     const dim3 grid((shape->ffn + 63) / 64, t.capacity);
     if (shape->dtype == LZ_F32) {
       if (swiglu)
         hipLaunchKernelGGL((gemm_generic_kernel<float, EPI_SWIGLU>), grid, dim3(256), 0, st, (const float*)xp,
-                           shape->d, (const float*)w1, n1, shape->ffn, shape->ffn, (float*)w.hidden, t);
+                           shape->d, (const float*)w1, n1, shape->ffn, shape->ffn, (float*)w.hidden, t, gather,
+                           gk, gT);
       else
         hipLaunchKernelGGL((gemm_generic_kernel<float, EPI_GELU>), grid, dim3(256), 0, st, (const float*)xp,
-                           shape->d, (const float*)w1, n1, shape->ffn, 0, (float*)w.hidden, t);
+                           shape->d, (const float*)w1, n1, shape->ffn, 0, (float*)w.hidden, t, gather, gk, gT);
     } else {
       if (swiglu)
         hipLaunchKernelGGL((gemm_generic_kernel<uint16_t, EPI_SWIGLU>), grid, dim3(256), 0, st,
                            (const uint16_t*)xp, shape->d, (const uint16_t*)w1, n1, shape->ffn, shape->ffn,
-                           (uint16_t*)w.hidden, t);
+                           (uint16_t*)w.hidden, t, gather, gk, gT);
       else
         hipLaunchKernelGGL((gemm_generic_kernel<uint16_t, EPI_GELU>), grid, dim3(256), 0, st,
                            (const uint16_t*)xp, shape->d, (const uint16_t*)w1, n1, shape->ffn, 0,
-                           (uint16_t*)w.hidden, t);
+                           (uint16_t*)w.hidden, t, gather, gk, gT);
     }
     return lz::launch_status();
   }
   if ((uintptr_t)xp % 16 != 0 || (uintptr_t)w1 % 16 != 0) return LZ_EINVAL;  // 16-byte loads per lane
+  // the MFMA gather addresses all of x with 32-bit byte offsets
+  if (gather && (unsigned long long)shape->T * shape->d * 2ull >= (1ull << 32)) return LZ_ESHAPE;
   MfmaArgs g1{};
   g1.A = (const uint16_t*)xp;
   g1.W = (const uint16_t*)w1;
@@ -218,7 +237,25 @@ extern "C" int32_t lz_ffn_up(const void* xp, const void* w1, const lz_shape* sha
   g1.which = 0;
   g1.t = t;
   g1.ldw = n1;
+  g1.gather = gather;
+  g1.gather_k = gk;
+  g1.gather_T = gT;
+  if (gather)
+    return swiglu ? launch_mfma<EPI_SWIGLU, MODE_NN, true>(g1, st) : launch_mfma<EPI_GELU, MODE_NN, true>(g1, st);
   return swiglu ? launch_mfma<EPI_SWIGLU, MODE_NN>(g1, st) : launch_mfma<EPI_GELU, MODE_NN>(g1, st);
+}
+
+}  // namespace
+
+extern "C" int32_t lz_ffn_up(const void* xp, const void* w1, const lz_shape* shape, void* ws,
+                             size_t ws_bytes, void* stream) {
+  return ffn_up(xp, nullptr, w1, shape, ws, ws_bytes, stream);
+}
+
+extern "C" int32_t lz_ffn_up_gather(const void* x, const int32_t* row_to_pair, const void* w1,
+                                    const lz_shape* shape, void* ws, size_t ws_bytes, void* stream) {
+  if (!row_to_pair && shape && (long long)shape->T * shape->k > 0) return LZ_EINVAL;
+  return ffn_up(x, row_to_pair, w1, shape, ws, ws_bytes, stream);
 }
 
 extern "C" int32_t lz_ffn_down(const void* w2, const lz_shape* shape, void* yp, void* ws,
@@ -236,11 +273,11 @@ extern "C" int32_t lz_ffn_down(const void* w2, const lz_shape* shape, void* yp, 
     if (shape->dtype == LZ_F32)
       hipLaunchKernelGGL((gemm_generic_kernel<float, EPI_NONE>), grid, dim3(256), 0, st,
                          (const float*)w.hidden, shape->ffn, (const float*)w2, shape->d, shape->d, 0,
-                         (float*)yp, t);
+                         (float*)yp, t, (const int32_t*)nullptr, 1, 0ll);
     else
       hipLaunchKernelGGL((gemm_generic_kernel<uint16_t, EPI_NONE>), grid, dim3(256), 0, st,
                          (const uint16_t*)w.hidden, shape->ffn, (const uint16_t*)w2, shape->d, shape->d, 0,
-                         (uint16_t*)yp, t);
+                         (uint16_t*)yp, t, (const int32_t*)nullptr, 1, 0ll);
     return lz::launch_status();
   }
   if ((uintptr_t)yp % 16 != 0 || (uintptr_t)w2 % 16 != 0) return LZ_EINVAL;  // 16-byte accesses per lane
@@ -269,6 +306,19 @@ extern "C" int32_t lz_expert_ffn(const void* xp, const int32_t* slot_offsets, co
   if (P == 0) return LZ_OK;
   if (!xp || !w1 || !w2 || !yp) return LZ_EINVAL;
   rc = lz_ffn_up(xp, w1, shape, ws, ws_bytes, stream);
+  if (rc != LZ_OK) return rc;
+  return lz_ffn_down(w2, shape, yp, ws, ws_bytes, stream);
+}
+
+extern "C" int32_t lz_expert_ffn_gather(const void* x, const int32_t* row_to_pair, const int32_t* slot_offsets,
+                                        const void* w1, const void* w2, const lz_shape* shape, void* yp,
+                                        void* ws, size_t ws_bytes, void* stream) {
+  int32_t rc = lz_ffn_tiles(slot_offsets, shape, ws, ws_bytes, stream);
+  if (rc != LZ_OK) return rc;
+  const long long P = (long long)shape->T * shape->k;
+  if (P == 0) return LZ_OK;
+  if (!x || !row_to_pair || !w1 || !w2 || !yp) return LZ_EINVAL;
+  rc = lz_ffn_up_gather(x, row_to_pair, w1, shape, ws, ws_bytes, stream);
   if (rc != LZ_OK) return rc;
   return lz_ffn_down(w2, shape, yp, ws, ws_bytes, stream);
 }

@@ -187,6 +187,11 @@ struct MfmaArgs {
   const int32_t* slot_offsets;
   long long k_rows;
   int rows_per_slot;
+  // GATHER (forward only): A is x [gather_T, K] and row r of the permuted buffer is row
+  // gather[r] / gather_k of it (gather = row_to_pair of the dispatcher)
+  const int32_t* gather;
+  int gather_k;
+  long long gather_T;
 };
 
 // Operand layouts of the contraction C[m, n] = sum_k A(m, k) W(n, k):
@@ -269,7 +274,7 @@ __device__ __forceinline__ void sched_slice() {
 // One output tile of 64*XF rows x 256 columns n of the weight operand W(n, k) ("weight rows"
 // below, whichever way W lies in memory).  XF = 32-row activation fragments per wave: the 2x2 waves each own (32*XF) x 128 of the tile, so a slot's ragged last tile costs
 // MFMAs and activation loads only for its rows rounded up to 64.
-template <int EPI, int XF, int MODE>
+template <int EPI, int XF, int MODE, bool GATHER>
 __device__ __forceinline__ void gemm_tile(const MfmaArgs& a, char* smem, int slot, int row0, int row_end, int n0) {
   constexpr bool TA = MODE == MODE_TN, TB = MODE != MODE_NT;  // k-major left / right operand
   constexpr bool kGated = EPI == EPI_SWIGLU || EPI == EPI_SWIGLU_KEEP;
@@ -306,8 +311,13 @@ __device__ __forceinline__ void gemm_tile(const MfmaArgs& a, char* smem, int slo
     stepA = 64 * a.lda * 2;
     stepW = 64 * a.ldw * 2;
   } else if constexpr (MODE == MODE_NN) {
-    tileA = a.A + (size_t)row0 * K;
-    a_extent = (uint32_t)n_rows * (uint32_t)K * 2u;
+    if constexpr (GATHER) {
+      tileA = a.A;  // the whole of x: a tile's rows lie anywhere in it (the host checked that it fits 32-bit offsets)
+      a_extent = (uint32_t)((unsigned long long)a.gather_T * (unsigned)K * 2ull);
+    } else {
+      tileA = a.A + (size_t)row0 * K;
+      a_extent = (uint32_t)n_rows * (uint32_t)K * 2u;
+    }
     tileW = a.W + (size_t)slot * K * a.ldw;
     w_extent = (uint32_t)K * (uint32_t)a.ldw * 2u;
     stepW = 64 * a.ldw * 2;
@@ -339,9 +349,24 @@ __device__ __forceinline__ void gemm_tile(const MfmaArgs& a, char* smem, int slo
     return (int)(((uint32_t)kr * (uint32_t)ld + (uint32_t)col0 + (uint32_t)piece * 8u) * 2u);
   };
   int voffX[kLoadsX], voffW[kLoadsW];
+  // GATHER: the activation rows are looked up through the row map.  The index loads go out first
+  // and are waited for only after the first weight loads have been issued (further down), so
+  // their latency hides behind the weights' way from HBM.
+  [[maybe_unused]] int gidx[kLoadsX];
+  if constexpr (GATHER) {
+    const i32x4 wordsG = rsrc_words(a.gather + row0, (uint32_t)n_rows * 4u);
+#pragma unroll
+    for (int i = 0; i < kLoadsX; ++i) {
+      const int r = (wave * kLoadsX + i) * 8 + (lane >> 3);
+      const int ga = r < n_rows ? r : n_rows - 1;
+      asm volatile("buffer_load_dword %0, %1, %2, 0 offen" : "=v"(gidx[i]) : "v"(ga * 4), "s"(wordsG) : "memory");
+    }
+  }
 #pragma unroll
   for (int i = 0; i < kLoadsX; ++i) {
-    if constexpr (TA) {
+    if constexpr (GATHER) {
+      voffX[i] = 0;  // set once the indices have arrived
+    } else if constexpr (TA) {
       voffX[i] = voff_kmajor(i, a.lda, 0);  // columns past the operand's edge fetch its neighbours: never stored
     } else {
       const int r = (wave * kLoadsX + i) * 8 + (lane >> 3);
@@ -506,7 +531,23 @@ __device__ __forceinline__ void gemm_tile(const MfmaArgs& a, char* smem, int slo
         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[set][i], xf[set][j], acc[i][j], 0, 0, 0);
   };
 
-  issue(0, 0, 0, kLoads);
+  if constexpr (GATHER) {
+    issue(0, 0, kLoadsX, kLoads);                        // the weight tile of step 0 does not need the row map
+    __builtin_amdgcn_s_waitcnt(0x0F70 | kLoadsW);        // vmcnt: the index loads (issued before those) are back
+    const uint32_t gk = (uint32_t)a.gather_k, n_pairs = (uint32_t)(a.gather_T * a.gather_k);
+#pragma unroll
+    for (int i = 0; i < kLoadsX; ++i) {
+      asm volatile("" : "+v"(gidx[i]));                  // nothing below may move above the wait
+      const int r = (wave * kLoadsX + i) * 8 + (lane >> 3);
+      const int chunk = (lane & 7) ^ swz(r);
+      const uint32_t pair = (uint32_t)gidx[i];
+      // a row without a pair (never inside a slot) reads past the descriptor's end: zeros
+      voffX[i] = pair < n_pairs ? (int)((pair / gk * (uint32_t)K + (uint32_t)chunk * 8u) * 2u) : (int)a_extent;
+    }
+    issue(0, 0, 0, kLoadsX);
+  } else {
+    issue(0, 0, 0, kLoads);
+  }
   issue(1, 1, 0, kAfterBarrier);
   // s_waitcnt with only vmcnt set (bits [3:0] and [15:14]): stage 1's first loads may still be in flight
   __builtin_amdgcn_s_waitcnt(0x0F70 | kAfterBarrier);
@@ -616,7 +657,7 @@ __device__ __forceinline__ void gemm_tile(const MfmaArgs& a, char* smem, int slo
 // its own pace.  (The hardware hands the workgroups of an ordinary launch to the XCDs strictly
 // in order of their index: there an XCD whose tiles take longer holds back the workgroups
 // queued behind it for every other XCD, which costs 10-40 % on ragged plans.)
-template <int EPI, int MODE = MODE_NT>
+template <int EPI, int MODE, bool GATHER>
 __global__ __launch_bounds__(256, 1) void gemm_mfma_kernel(MfmaArgs a) {
 #if defined(__HIP_DEVICE_COMPILE__)  // the host pass only needs the launch stub, not the gfx950 builtins
   extern __shared__ __attribute__((aligned(1024))) char smem[];
@@ -648,10 +689,10 @@ __global__ __launch_bounds__(256, 1) void gemm_mfma_kernel(MfmaArgs a) {
       const int row_end = a.t.row_end[row_tile];
       const int n0 = nt * BN_OUT;
       const int rows = row_end - row0;  // > 0; more than 256 means a full tile
-      if (rows > 192) gemm_tile<EPI, 4, MODE>(a, smem, slot, row0, row_end, n0);
-      else if (rows > 128) gemm_tile<EPI, 3, MODE>(a, smem, slot, row0, row_end, n0);
-      else if (rows > 64) gemm_tile<EPI, 2, MODE>(a, smem, slot, row0, row_end, n0);
-      else gemm_tile<EPI, 1, MODE>(a, smem, slot, row0, row_end, n0);
+      if (rows > 192) gemm_tile<EPI, 4, MODE, GATHER>(a, smem, slot, row0, row_end, n0);
+      else if (rows > 128) gemm_tile<EPI, 3, MODE, GATHER>(a, smem, slot, row0, row_end, n0);
+      else if (rows > 64) gemm_tile<EPI, 2, MODE, GATHER>(a, smem, slot, row0, row_end, n0);
+      else gemm_tile<EPI, 1, MODE, GATHER>(a, smem, slot, row0, row_end, n0);
     }
   }
   // the last workgroup to finish leaves the tickets at zero for the next launch on this table
@@ -665,9 +706,10 @@ __global__ __launch_bounds__(256, 1) void gemm_mfma_kernel(MfmaArgs a) {
 #endif
 }
 
-template <int EPI, int MODE = MODE_NT>
+template <int EPI, int MODE = MODE_NT, bool GATHER = false>
 int32_t launch_mfma(const MfmaArgs& a, hipStream_t st) {
-  void (*kern)(MfmaArgs) = gemm_mfma_kernel<EPI, MODE>;
+  static_assert(!GATHER || MODE == MODE_NN, "the gather is part of the forward's first GEMM only");
+  void (*kern)(MfmaArgs) = gemm_mfma_kernel<EPI, MODE, GATHER>;
   static bool configured = false;  // per-process attribute; idempotent, so a benign race at worst
   static int n_workgroups = 0;
   if (!configured) {
