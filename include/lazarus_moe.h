@@ -231,11 +231,13 @@ int32_t lz_unpermute_combine(const void* yp, const int32_t* pair_to_row,
  *   lz_route_backward     dlogits[t, ids[t,j]] = g_j (dg_j - sum_i g_i dg_i), 0 elsewhere
  *   lz_reduce_replica_grads   dW[e] = sum of dW[s] over the slots s holding expert e
  *
- * bf16 tensors only (LZ_ESHAPE otherwise), products accumulated in fp32, every stored tensor
- * rounded to bf16 once.  The FFN calls need d % 256 == 0, ffn % 64 == 0, d*ffn*4 < 2^31,
- * T*k*max(d, 2*ffn)*2 < 2^31 and N*c*max(d, 2*ffn) < 2^31.  All tensor pointers are device memory, 16-byte
- * aligned; `ws` is 256-byte aligned device memory of lz_train_workspace_bytes(shape) bytes that
- * serves one call at a time. */
+ * Products are accumulated in fp32 and every stored tensor is rounded once to shape->dtype.
+ * bf16 shapes with d % 256 == 0, ffn % 64 == 0, d*ffn*4 < 2^31, T*k*max(d, 2*ffn)*2 < 2^31 and
+ * N*c*max(d, 2*ffn) < 2^31 run on the MFMA kernels (tensor pointers 16-byte aligned there);
+ * every other valid shape (fp32 tensors, other bf16 sizes) runs on plain tiled fp32-FMA kernels
+ * that use erff / expf (the fp32 configuration meets its 1e-5 bar), as long as T*k/64 + N*c is
+ * at most 65535.  All tensor pointers are device memory; `ws` is 256-byte aligned device memory of
+ * lz_train_workspace_bytes(shape) bytes that serves one call at a time. */
 size_t lz_train_workspace_bytes(const lz_shape* shape);
 
 /* lz_expert_ffn that also returns what the backward needs: z = xp W1 (pre-activation,
@@ -248,7 +250,7 @@ int32_t lz_ffn_forward_train(const void* xp, const int32_t* slot_offsets, const 
                              void* stream);
 
 /* Backward of lz_unpermute_combine.  A dyp row that no pair maps to is left untouched.
- *   dy dev [T,d], yp dev [P,d], dyp dev [P,d] out, dgates dev [T,k] f32 out */
+ *   dy dev [T,d], yp dev [P,d], dyp dev [P,d] out (all of shape->dtype), dgates dev [T,k] f32 out */
 int32_t lz_combine_backward(const void* dy, const void* yp, const int32_t* pair_to_row,
                             const float* topk_gates, const lz_shape* shape, void* dyp, float* dgates,
                             void* stream);
@@ -278,9 +280,12 @@ int32_t lz_route_backward(const float* dgates, const float* topk_gates, const in
  * replicas that live on one device: dw[e] = sum over slots s with slot_expert[s] == e of
  * dw_slot[s], ascending s, fp32 sum, one rounding; an expert without a slot gets zero.
  *   dw_slot dev [S, elems_per_slot] bf16, slot_expert dev [S] i32, dw dev [E, elems_per_slot] bf16 out;
- *   elems_per_slot % 8 == 0 */
+ *   elems_per_slot % 8 == 0, pointers 16-byte aligned
+ * lz_reduce_replica_grads_dtype: the same for LZ_F32 or LZ_BF16 tensors of any size and alignment. */
 int32_t lz_reduce_replica_grads(const void* dw_slot, const int32_t* slot_expert, int32_t S, int32_t E,
                                 int64_t elems_per_slot, void* dw, void* stream);
+int32_t lz_reduce_replica_grads_dtype(const void* dw_slot, const int32_t* slot_expert, int32_t S, int32_t E,
+                                      int64_t elems_per_slot, int32_t dtype, void* dw, void* stream);
 
 /* ---------------------------------------------------------------- host planning */
 

@@ -15,6 +15,7 @@ __all__ = [
     "lz_replan", "lz_apply_transfers", "MoELayer",
     "lz_pack_weights", "lz_train_workspace_bytes", "lz_ffn_forward_train", "lz_combine_backward",
     "lz_ffn_backward", "lz_permute_backward", "lz_route_backward", "lz_reduce_replica_grads",
+    "lz_reduce_replica_grads_dtype",
 ]
 
 LZ_F32, LZ_BF16 = 0, 1
@@ -123,6 +124,7 @@ def _load():
         "lz_permute_backward": (i32, [vp, vp, sp, vp, vp]),
         "lz_route_backward": (i32, [vp, vp, vp, sp, vp, vp]),
         "lz_reduce_replica_grads": (i32, [vp, vp, i32, i32, C.c_int64, vp, vp]),
+        "lz_reduce_replica_grads_dtype": (i32, [vp, vp, i32, i32, C.c_int64, i32, vp, vp]),
     }
     for name, (res, args) in sig.items():
         fn = getattr(L, name)
@@ -281,6 +283,12 @@ def lz_route_backward(dgates, topk_gates, topk_ids, shape, dlogits, stream=None)
 def lz_reduce_replica_grads(dw_slot, slot_expert, S, E, elems_per_slot, dw, stream=None):
     _check(lib.lz_reduce_replica_grads(_ptr(dw_slot), _ptr(slot_expert), S, E, elems_per_slot, _ptr(dw),
                                        _stream() if stream is None else stream), "lz_reduce_replica_grads")
+
+
+def lz_reduce_replica_grads_dtype(dw_slot, slot_expert, S, E, elems_per_slot, dtype, dw, stream=None):
+    _check(lib.lz_reduce_replica_grads_dtype(_ptr(dw_slot), _ptr(slot_expert), S, E, elems_per_slot, dtype, _ptr(dw),
+                                             _stream() if stream is None else stream),
+           "lz_reduce_replica_grads_dtype")
 
 
 # ------------------------------------------------------------------ host planning
@@ -457,10 +465,10 @@ class MoELayer:
 
     # ---- training: forward that keeps its intermediates, then the backward chain
     def enable_training(self):
-        """Allocate what the backward needs (bf16 MFMA shapes only)."""
+        """Allocate what the backward needs."""
         import torch
         s, dev = self.shape, self.device
-        bf = torch.bfloat16
+        bf = torch.float32 if s.dtype == LZ_F32 else torch.bfloat16
         n1 = self.w1.shape[2]
         self.train_ws_bytes = lz_train_workspace_bytes(s)
         if self.train_ws_bytes == 0:
@@ -503,6 +511,8 @@ class MoELayer:
                         self.dw1_slot, self.dw2_slot, self.train_ws, self.train_ws_bytes)
         lz_permute_backward(self.dxp, self.pair_to_row, s, self.dx)
         lz_route_backward(self.dgates, self.topk_gates, self.topk_ids, s, self.dlogits)
-        lz_reduce_replica_grads(self.dw1_slot, self.slot_expert, s.S, s.E, self.dw1_slot[0].numel(), self.dw1)
-        lz_reduce_replica_grads(self.dw2_slot, self.slot_expert, s.S, s.E, self.dw2_slot[0].numel(), self.dw2)
+        lz_reduce_replica_grads_dtype(self.dw1_slot, self.slot_expert, s.S, s.E, self.dw1_slot[0].numel(), s.dtype,
+                                      self.dw1)
+        lz_reduce_replica_grads_dtype(self.dw2_slot, self.slot_expert, s.S, s.E, self.dw2_slot[0].numel(), s.dtype,
+                                      self.dw2)
         return self.dx

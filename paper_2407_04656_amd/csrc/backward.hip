@@ -19,6 +19,7 @@
 // reads): no transposed copy of weights or activations is ever written.  The weight gradients
 // run over S x (rows of the weight matrix) virtual rows; each tile takes its contraction range
 // from slot_offsets.
+#include "backward_generic.h"
 #include "gemm_mfma.h"
 
 namespace {
@@ -322,16 +323,40 @@ int32_t gemm_wgrad(const uint16_t* A, const uint16_t* W, uint16_t* C, int S, lon
   return launch_mfma<EPI_NONE, MODE_TN>(g, st);
 }
 
+// the generic path takes every valid shape whose 64-row tile count fits a grid dimension
+inline bool generic_train_shape(const lz_shape* s) {
+  if (!lz::shape_ok(s)) return false;
+  return tile_capacity((long long)s->T * s->k, s->N * s->c, 64, 1) <= 65535;
+}
+
+int32_t check_train_generic(const lz_shape* shape, void* ws, size_t ws_bytes, GenericTrainWorkspace* w) {
+  if (!generic_train_shape(shape)) return LZ_ESHAPE;
+  *w = carve_train_generic(ws, shape);
+  if (!ws || (uintptr_t)ws % 256 != 0 || ws_bytes < w->total_bytes) return LZ_EWORKSPACE;
+  return LZ_OK;
+}
+
 }  // namespace
 
 extern "C" size_t lz_train_workspace_bytes(const lz_shape* shape) {
-  if (!train_shape(shape)) return 0;
-  return carve_train(nullptr, shape).total_bytes;
+  if (train_shape(shape)) return carve_train(nullptr, shape).total_bytes;
+  if (generic_train_shape(shape)) return carve_train_generic(nullptr, shape).total_bytes;
+  return 0;
 }
 
 extern "C" int32_t lz_ffn_forward_train(const void* xp, const int32_t* slot_offsets, const void* w1, const void* w2,
                                         const lz_shape* shape, void* z, void* h, void* yp, void* ws,
                                         size_t ws_bytes, void* stream) {
+  if (!train_shape(shape)) {
+    GenericTrainWorkspace gw;
+    const int32_t grc = check_train_generic(shape, ws, ws_bytes, &gw);
+    if (grc != LZ_OK) return grc;
+    if ((long long)shape->T * shape->k == 0) return LZ_OK;
+    if (!xp || !slot_offsets || !w1 || !w2 || !z || !h || !yp) return LZ_EINVAL;
+    return shape->dtype == LZ_F32
+               ? generic_forward_train<float>(xp, slot_offsets, w1, w2, shape, z, h, yp, gw, (hipStream_t)stream)
+               : generic_forward_train<uint16_t>(xp, slot_offsets, w1, w2, shape, z, h, yp, gw, (hipStream_t)stream);
+  }
   TrainWorkspace w;
   const int32_t rc = check_train(shape, ws, ws_bytes, &w);
   if (rc != LZ_OK) return rc;
@@ -372,12 +397,22 @@ extern "C" int32_t lz_combine_backward(const void* dy, const void* yp, const int
                                        const float* topk_gates, const lz_shape* shape, void* dyp, float* dgates,
                                        void* stream) {
   if (!lz::shape_ok(shape)) return LZ_ESHAPE;
-  if (shape->dtype != LZ_BF16 || shape->d % 8 != 0) return LZ_ESHAPE;
   if (shape->T == 0) return LZ_OK;
   if (!dy || !yp || !pair_to_row || !topk_gates || !dyp || !dgates) return LZ_EINVAL;
-  if (!aligned16(dy) || !aligned16(yp) || !aligned16(dyp)) return LZ_EINVAL;
   const long long P = (long long)shape->T * shape->k;
   const unsigned blocks = unsigned((shape->T + kRowsPerBlock - 1) / kRowsPerBlock);
+  if (shape->dtype != LZ_BF16 || shape->d % 8 != 0 || !aligned16(dy) || !aligned16(yp) || !aligned16(dyp)) {
+    // element-wise kernel: fp32 tensors, rows that are not a multiple of 16 bytes, unaligned buffers
+    if (shape->dtype == LZ_F32)
+      hipLaunchKernelGGL(combine_backward_generic_kernel<float>, dim3(blocks), dim3(256), 0, (hipStream_t)stream,
+                         (const float*)dy, (const float*)yp, pair_to_row, topk_gates, shape->T, shape->k, P,
+                         shape->d, (float*)dyp, dgates);
+    else
+      hipLaunchKernelGGL(combine_backward_generic_kernel<uint16_t>, dim3(blocks), dim3(256), 0, (hipStream_t)stream,
+                         (const uint16_t*)dy, (const uint16_t*)yp, pair_to_row, topk_gates, shape->T, shape->k, P,
+                         shape->d, (uint16_t*)dyp, dgates);
+    return lz::launch_status();
+  }
   hipLaunchKernelGGL(combine_backward_kernel, dim3(blocks), dim3(256), 0, (hipStream_t)stream, (const u32x4*)dy,
                      (const u32x4*)yp, pair_to_row, topk_gates, shape->T, shape->k, P, shape->d / 8, (u32x4*)dyp,
                      dgates);
@@ -399,6 +434,18 @@ extern "C" int32_t lz_ffn_backward(const void* dyp, const void* xp, const void* 
                                    const int32_t* slot_offsets, const void* w1, const void* w2,
                                    const lz_shape* shape, void* dxp, void* dw1, void* dw2, void* ws,
                                    size_t ws_bytes, void* stream) {
+  if (!train_shape(shape)) {
+    GenericTrainWorkspace gw;
+    const int32_t grc = check_train_generic(shape, ws, ws_bytes, &gw);
+    if (grc != LZ_OK) return grc;
+    if (!dw1 || !dw2 || !slot_offsets) return LZ_EINVAL;
+    if ((long long)shape->T * shape->k > 0 && (!dyp || !xp || !z || !h || !w1 || !w2 || !dxp)) return LZ_EINVAL;
+    return shape->dtype == LZ_F32
+               ? generic_ffn_backward<float>(dyp, xp, z, h, slot_offsets, w1, w2, shape, dxp, dw1, dw2, gw,
+                                             (hipStream_t)stream)
+               : generic_ffn_backward<uint16_t>(dyp, xp, z, h, slot_offsets, w1, w2, shape, dxp, dw1, dw2, gw,
+                                                (hipStream_t)stream);
+  }
   TrainWorkspace w;
   const int32_t rc = check_train(shape, ws, ws_bytes, &w);
   if (rc != LZ_OK) return rc;
@@ -454,5 +501,25 @@ extern "C" int32_t lz_reduce_replica_grads(const void* dw_slot, const int32_t* s
   if ((vec + 255) / 256 > 0x7FFFFFFFll) return LZ_ESHAPE;
   hipLaunchKernelGGL(reduce_replicas_kernel, dim3((unsigned)((vec + 255) / 256), (unsigned)E), dim3(256), 0,
                      (hipStream_t)stream, (const u32x4*)dw_slot, slot_expert, S, vec, (u32x4*)dw);
+  return lz::launch_status();
+}
+
+extern "C" int32_t lz_reduce_replica_grads_dtype(const void* dw_slot, const int32_t* slot_expert, int32_t S,
+                                                 int32_t E, int64_t elems_per_slot, int32_t dtype, void* dw,
+                                                 void* stream) {
+  if (dtype != LZ_F32 && dtype != LZ_BF16) return LZ_ESHAPE;
+  if (dtype == LZ_BF16 && elems_per_slot % 8 == 0 && aligned16(dw_slot) && aligned16(dw))
+    return lz_reduce_replica_grads(dw_slot, slot_expert, S, E, elems_per_slot, dw, stream);
+  if (S < 1 || E < 1 || E > 65535 || elems_per_slot < 0) return LZ_ESHAPE;
+  if (elems_per_slot == 0) return LZ_OK;
+  if (!dw_slot || !slot_expert || !dw) return LZ_EINVAL;
+  if ((elems_per_slot + 255) / 256 > 0x7FFFFFFFll) return LZ_ESHAPE;
+  const dim3 grid((unsigned)((elems_per_slot + 255) / 256), (unsigned)E);
+  if (dtype == LZ_F32)
+    hipLaunchKernelGGL(reduce_replicas_generic_kernel<float>, grid, dim3(256), 0, (hipStream_t)stream,
+                       (const float*)dw_slot, slot_expert, S, (long long)elems_per_slot, (float*)dw);
+  else
+    hipLaunchKernelGGL(reduce_replicas_generic_kernel<uint16_t>, grid, dim3(256), 0, (hipStream_t)stream,
+                       (const uint16_t*)dw_slot, slot_expert, S, (long long)elems_per_slot, (uint16_t*)dw);
   return lz::launch_status();
 }

@@ -389,11 +389,70 @@ def test_backward_without_tokens_and_with_bad_offsets():
     assert not outs[0][2][1].any().item() and not outs[0][3][3].any().item()      # the empty slots
 
 
+def _layer_backward_generic(cfg, tol):
+    """Whole layer forward + backward through MoELayer on a shape the MFMA kernels do not serve."""
+    inp = step_inputs(cfg)
+    w = expert_weights(cfg, threads=4)
+    ids, gates = om.route(inp["logits"], cfg.k)
+    plan = oracle_plan(cfg, ids)
+    disp = om.plan_dispatch(ids, inp["rank_tok_off"], plan, cfg.E, cfg.N, cfg.c)
+    shape = lz.Shape.from_config(cfg)
+    bf16 = cfg.dtype == "bf16"
+    layer = lz.MoELayer(shape, DEV)
+    layer.load_expert_weights(w["w1"], w["w2"], plan)
+    layer.set_plan(plan, inp["rank_tok_off"])
+    layer.enable_training()
+    rng = np.random.default_rng(21)
+    dy = rng.standard_normal((cfg.T, cfg.d)).astype(np.float32)
+    dy = f32_to_bf16_bits(dy) if bf16 else dy
+    y = layer.forward_train(to_dev(inp["logits"]), to_dev(inp["x"], bf16))
+    layer.backward(to_dev(dy, bf16))
+    torch.cuda.synchronize()
+    assert np.array_equal(to_host(layer.pair_to_row), disp["pair_to_row"])
+    assert rel_err(to_host(y), om.layer_output(inp["x"], ids, gates, w["w1"], w["w2"], cfg.act)) <= tol
+    ref = ob.layer_backward(dy, inp["x"], ids, gates, disp["pair_to_row"], disp["row_to_pair"],
+                            disp["slot_offsets"], plan, w["w1"], w["w2"], cfg.act)
+    assert rel_err(to_host(layer.dx), ref["dx"]) <= tol
+    assert rel_err(to_host(layer.dgates), ref["dgates"]) <= tol
+    assert rel_err(to_host(layer.dw1), ref["dw1"].transpose(0, 2, 1)) <= tol     # oracle: [out, in]
+    assert rel_err(to_host(layer.dw2), ref["dw2"].transpose(0, 2, 1)) <= tol
+    assert rel_err(to_host(layer.dlogits), ob.route_backward(ref["dgates"], gates, ids, cfg.E)) <= tol
+    # the kept intermediates against the oracle's
+    Xp = om.widen(om.permute(inp["x"], disp["row_to_pair"], cfg.k))
+    off = disp["slot_offsets"]
+    Zref = np.zeros((cfg.T * cfg.k, to_host(layer.z).shape[1]))
+    for s_ in range(cfg.N * cfg.c):
+        a_, b_ = off[s_], off[s_ + 1]
+        Zref[a_:b_] = Xp[a_:b_] @ om.widen(w["w1"][plan[s_]]).T
+    assert rel_err(to_host(layer.z), Zref) <= tol
+    assert rel_err(to_host(layer.h), ob.act_forward(Zref, cfg.act)) <= tol
+    # experts without a slot cannot occur; an expert's gradient is the sum over its replicas
+    return layer
+
+
+def test_layer_backward_fp32_config_1():
+    """Config 1 (fp32, GELU, fixed replica counts, spread placement) in full through the training
+    entry points: the plain tiled fp32 kernels meet the fp32 error bar of the forward."""
+    _layer_backward_generic(CONFIGS["c1_tiny"], 1e-5)
+
+
+@pytest.mark.parametrize("act,dtype,tol", [("swiglu", "f32", 1e-5), ("gelu", "bf16", 2e-2), ("swiglu", "bf16", 2e-2)])
+def test_layer_backward_generic_shapes(act, dtype, tol):
+    """Sizes the MFMA tiling does not divide (d = 72, ffn = 200, top-3, ragged ranks), both dtypes."""
+    cfg = scaled(CONFIGS["c1_tiny"], act=act, dtype=dtype, T=333, d=72, ffn=200, E=8, k=3, N=3, c=4,
+                 replica_counts=(2, 2, 2, 2, 1, 1, 1, 1))
+    _layer_backward_generic(cfg, tol)
+
+
 def test_training_entry_points_reject_what_they_do_not_serve():
+    bad = lz.Shape(T=16, d=8, ffn=8, E=4, k=9, N=2, c=2, dtype=lz.LZ_F32, act=lz.LZ_GELU)
+    assert lz.lz_train_workspace_bytes(bad) == 0
     f32 = lz.Shape.from_config(CONFIGS["c1_tiny"])
-    assert lz.lz_train_workspace_bytes(f32) == 0
+    assert lz.lz_train_workspace_bytes(f32) > 0          # generic kernels
     odd = lz.Shape.from_config(scaled(CONFIGS["c1_tiny"], dtype="bf16", d=264, ffn=128))
-    assert lz.lz_train_workspace_bytes(odd) == 0
+    assert lz.lz_train_workspace_bytes(odd) > 0
+    huge = lz.Shape.from_config(scaled(CONFIGS["c1_tiny"], T=1 << 23, k=2, d=264, ffn=128))
+    assert lz.lz_train_workspace_bytes(huge) == 0        # too many 64-row tiles for the generic path
     ok = lz.Shape.from_config(scaled(CONFIGS["c1_tiny"], dtype="bf16", d=256, ffn=128))
     n = lz.lz_train_workspace_bytes(ok)
     ws = torch.empty(n, dtype=torch.uint8, device=DEV)
@@ -402,5 +461,8 @@ def test_training_entry_points_reject_what_they_do_not_serve():
         lz.lz_ffn_backward(dummy, dummy, dummy, dummy, dummy, dummy, dummy, ok, dummy, dummy, dummy, ws, n - 256)
     assert e.value.code == -3
     with pytest.raises(lz.LzError) as e:
-        lz.lz_ffn_backward(dummy, dummy, dummy, dummy, dummy, dummy, dummy, f32, dummy, dummy, dummy, ws, n)
+        lz.lz_ffn_backward(dummy, dummy, dummy, dummy, dummy, dummy, dummy, bad, dummy, dummy, dummy, ws, n)
     assert e.value.code == -2
+    with pytest.raises(lz.LzError) as e:
+        lz.lz_ffn_backward(dummy, dummy, dummy, dummy, dummy, dummy, dummy, f32, dummy, dummy, dummy, ws, 256)
+    assert e.value.code == -3

@@ -147,8 +147,15 @@ def test_training_calls_validate_arguments_without_a_gpu():
     n = lz.lz_train_workspace_bytes(ok)
     # at least the two gradient intermediates dH [P, ffn] and dZ [P, 2 ffn]
     assert n >= ok.P * ok.ffn * 2 + ok.P * 2 * ok.ffn * 2
-    for bad in (shape(dtype=lz.LZ_F32), shape(d=264), shape(ffn=100), shape(k=9),
-                shape(T=1 << 20, k=8, d=4096, ffn=14336)):          # 32-bit offsets into a slot's rows
+    # served by the plain tiled kernels: fp32, sizes the MFMA tiling does not divide
+    for generic in (shape(dtype=lz.LZ_F32), shape(d=264), shape(ffn=100)):
+        assert lz.lz_train_workspace_bytes(generic) > 0
+        with pytest.raises(lz.LzError) as ei:                        # no workspace
+            lz.lz_ffn_backward(None, None, None, None, None, None, None, generic, None, None, None, None, 0, stream=0)
+        assert ei.value.code == -3
+    # invalid, or beyond both paths (32-bit offsets into a slot's rows on the MFMA path, and too many
+    # 64-row tiles for the plain one)
+    for bad in (shape(k=9), shape(T=1 << 20, k=8, d=4096, ffn=14336)):
         assert lz.lz_train_workspace_bytes(bad) == 0
         with pytest.raises(lz.LzError) as ei:
             lz.lz_ffn_backward(None, None, None, None, None, None, None, bad, None, None, None, None, 0, stream=0)
@@ -163,7 +170,7 @@ def test_training_calls_validate_arguments_without_a_gpu():
         lz.lz_combine_backward(None, None, None, None, ok, None, None, stream=0)
     assert ei.value.code == -1
     with pytest.raises(lz.LzError) as ei:
-        lz.lz_combine_backward(None, None, None, None, shape(dtype=lz.LZ_F32), None, None, stream=0)
+        lz.lz_combine_backward(None, None, None, None, shape(k=9), None, None, stream=0)
     assert ei.value.code == -2
     with pytest.raises(lz.LzError) as ei:
         lz.lz_route_backward(None, None, None, ok, None, stream=0)
