@@ -232,8 +232,8 @@ int32_t lz_unpermute_combine(const void* yp, const int32_t* pair_to_row,
  *   lz_reduce_replica_grads   dW[e] = sum of dW[s] over the slots s holding expert e
  *
  * Products are accumulated in fp32 and every stored tensor is rounded once to shape->dtype.
- * bf16 shapes with d % 256 == 0, ffn % 64 == 0, d*ffn*4 < 2^31, T*k*max(d, 2*ffn)*2 < 2^31 and
- * N*c*max(d, 2*ffn) < 2^31 run on the MFMA kernels (tensor pointers 16-byte aligned there);
+ * bf16 shapes with d % 256 == 0, ffn % 64 == 0, d*ffn*4 < 2^31 and N*c*max(d, 2*ffn) < 2^31 run on
+ * the MFMA kernels, whatever the size of the activation tensors (tensor pointers 16-byte aligned there);
  * every other valid shape (fp32 tensors, other bf16 sizes) runs on plain tiled fp32-FMA kernels
  * that use erff / expf (the fp32 configuration meets its 1e-5 bar), as long as T*k/64 + N*c is
  * at most 65535.  All tensor pointers are device memory; `ws` is 256-byte aligned device memory of
@@ -265,6 +265,16 @@ int32_t lz_ffn_backward(const void* dyp, const void* xp, const void* z, const vo
                         const int32_t* slot_offsets, const void* w1, const void* w2,
                         const lz_shape* shape, void* dxp, void* dw1, void* dw2, void* ws,
                         size_t ws_bytes, void* stream);
+
+/* lz_ffn_backward for training with micro-batches: the same computation, but each slot's weight
+ * gradients are ADDED to fp32 accumulators instead of being stored (rounded) in the training dtype:
+ *   dw1_acc dev [S,d,n1] f32, dw2_acc dev [S,ffn,d] f32 (in/out; the caller zeroes them before the
+ *   first micro-batch; an empty slot adds nothing); 16-byte aligned.
+ * lz_reduce_replica_grads_dtype(..., LZ_F32, ...) sums the accumulators over an expert's replicas. */
+int32_t lz_ffn_backward_accumulate(const void* dyp, const void* xp, const void* z, const void* h,
+                                   const int32_t* slot_offsets, const void* w1, const void* w2,
+                                   const lz_shape* shape, void* dxp, float* dw1_acc, float* dw2_acc,
+                                   void* ws, size_t ws_bytes, void* stream);
 
 /* Backward of the reshuffle: dx[t,:] = sum_{kk<k} dxp[pair_to_row[t*k+kk], :], fp32 sum in
  * ascending kk, rounded once.  Same dtypes as lz_unpermute_combine.  dxp dev [P,d], dx dev [T,d] out. */

@@ -14,7 +14,7 @@ __all__ = [
     "lz_ffn_tiles", "lz_ffn_up", "lz_ffn_down", "lz_ffn_up_gather", "lz_expert_ffn_gather", "lz_allocate_replicas", "lz_place_mro", "lz_place_spread", "lz_place_compact", "lz_recovery_probability",
     "lz_replan", "lz_apply_transfers", "MoELayer",
     "lz_pack_weights", "lz_train_workspace_bytes", "lz_ffn_forward_train", "lz_combine_backward",
-    "lz_ffn_backward", "lz_permute_backward", "lz_route_backward", "lz_reduce_replica_grads",
+    "lz_ffn_backward", "lz_ffn_backward_accumulate", "lz_permute_backward", "lz_route_backward", "lz_reduce_replica_grads",
     "lz_reduce_replica_grads_dtype",
 ]
 
@@ -121,6 +121,7 @@ def _load():
         "lz_ffn_forward_train": (i32, [vp, vp, vp, vp, sp, vp, vp, vp, vp, u64, vp]),
         "lz_combine_backward": (i32, [vp, vp, vp, vp, sp, vp, vp, vp]),
         "lz_ffn_backward": (i32, [vp, vp, vp, vp, vp, vp, vp, sp, vp, vp, vp, vp, u64, vp]),
+        "lz_ffn_backward_accumulate": (i32, [vp, vp, vp, vp, vp, vp, vp, sp, vp, vp, vp, vp, u64, vp]),
         "lz_permute_backward": (i32, [vp, vp, sp, vp, vp]),
         "lz_route_backward": (i32, [vp, vp, vp, sp, vp, vp]),
         "lz_reduce_replica_grads": (i32, [vp, vp, i32, i32, C.c_int64, vp, vp]),
@@ -268,6 +269,14 @@ def lz_ffn_backward(dyp, xp, z, h, slot_offsets, w1, w2, shape, dxp, dw1, dw2, w
     _check(lib.lz_ffn_backward(_ptr(dyp), _ptr(xp), _ptr(z), _ptr(h), _ptr(slot_offsets), _ptr(w1), _ptr(w2),
                                C.byref(shape.c_struct()), _ptr(dxp), _ptr(dw1), _ptr(dw2), _ptr(ws), ws_bytes,
                                _stream() if stream is None else stream), "lz_ffn_backward")
+
+
+def lz_ffn_backward_accumulate(dyp, xp, z, h, slot_offsets, w1, w2, shape, dxp, dw1_acc, dw2_acc, ws, ws_bytes,
+                               stream=None):
+    _check(lib.lz_ffn_backward_accumulate(_ptr(dyp), _ptr(xp), _ptr(z), _ptr(h), _ptr(slot_offsets), _ptr(w1),
+                                          _ptr(w2), C.byref(shape.c_struct()), _ptr(dxp), _ptr(dw1_acc),
+                                          _ptr(dw2_acc), _ptr(ws), ws_bytes,
+                                          _stream() if stream is None else stream), "lz_ffn_backward_accumulate")
 
 
 def lz_permute_backward(dxp, pair_to_row, shape, dx, stream=None):
@@ -503,6 +512,33 @@ class MoELayer:
                              self.train_ws, self.train_ws_bytes)
         self.unpermute_combine()
         return self.y
+
+    def enable_accumulation(self):
+        """fp32 accumulators for the slots' weight gradients (micro-batches), zeroed."""
+        import torch
+        self.dw1_acc = torch.zeros(tuple(self.dw1_slot.shape), dtype=torch.float32, device=self.device)
+        self.dw2_acc = torch.zeros(tuple(self.dw2_slot.shape), dtype=torch.float32, device=self.device)
+        self.dw1_sum = torch.empty(tuple(self.dw1.shape), dtype=torch.float32, device=self.device)
+        self.dw2_sum = torch.empty(tuple(self.dw2.shape), dtype=torch.float32, device=self.device)
+
+    def backward_accumulate(self, dy):
+        """One micro-batch: data gradients as in backward(), weight gradients added to the fp32 accumulators."""
+        s = self.shape
+        lz_combine_backward(dy, self.yp, self.pair_to_row, self.topk_gates, s, self.dyp, self.dgates)
+        lz_ffn_backward_accumulate(self.dyp, self.xp, self.z, self.h, self.slot_offsets, self.w1, self.w2, s,
+                                   self.dxp, self.dw1_acc, self.dw2_acc, self.train_ws, self.train_ws_bytes)
+        lz_permute_backward(self.dxp, self.pair_to_row, s, self.dx)
+        lz_route_backward(self.dgates, self.topk_gates, self.topk_ids, s, self.dlogits)
+        return self.dx
+
+    def reduce_accumulated(self):
+        """Per-expert sums of the accumulators over the replicas (fp32)."""
+        s = self.shape
+        lz_reduce_replica_grads_dtype(self.dw1_acc, self.slot_expert, s.S, s.E, self.dw1_acc[0].numel(), LZ_F32,
+                                      self.dw1_sum)
+        lz_reduce_replica_grads_dtype(self.dw2_acc, self.slot_expert, s.S, s.E, self.dw2_acc[0].numel(), LZ_F32,
+                                      self.dw2_sum)
+        return self.dw1_sum, self.dw2_sum
 
     def backward(self, dy):
         s = self.shape

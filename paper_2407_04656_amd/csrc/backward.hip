@@ -242,13 +242,11 @@ TrainWorkspace carve_train(void* ws, const lz_shape* s) {
   return w;
 }
 
-// the shapes the MFMA kernel serves: bf16, d a multiple of 256, ffn of 64, 32-bit offsets
+// the shapes the MFMA kernel serves: bf16, d a multiple of 256, ffn of 64, a slot's weights within 32-bit offsets
 inline bool train_shape(const lz_shape* s) {
   if (!lz::shape_ok(s) || s->dtype != LZ_BF16) return false;
   if (s->d % BN != 0 || s->ffn % 64 != 0) return false;
   if ((long long)s->d * s->ffn * 4 >= (1ll << 31)) return false;
-  // a slot's rows of a k-major operand are addressed with 32-bit byte offsets
-  if ((long long)s->T * s->k * (s->d > 2 * s->ffn ? s->d : 2 * s->ffn) * 2 >= (1ll << 31)) return false;
   const long long S = (long long)s->N * s->c;
   return S * s->d * 2 < (1ll << 31) && S * s->ffn * 2 < (1ll << 31);  // virtual row indices are int32
 }
@@ -302,13 +300,15 @@ int32_t gemm_nn(const uint16_t* A, const uint16_t* W, uint16_t* C, long long P, 
   return launch_mfma<EPI_NONE, MODE_NN>(g, st);
 }
 
-// dW[s] [rows_per_slot, n_out] = A[rows of s, :rows_per_slot]^T W[rows of s, :n_out]
-int32_t gemm_wgrad(const uint16_t* A, const uint16_t* W, uint16_t* C, int S, long long P, int rows_per_slot,
-                   int n_out, const int32_t* slot_offsets, const TileTable& t, hipStream_t st) {
+// dW[s] [rows_per_slot, n_out] = A[rows of s, :rows_per_slot]^T W[rows of s, :n_out], stored as bf16 in C,
+// or, if Cacc is given, added to that fp32 matrix instead
+int32_t gemm_wgrad(const uint16_t* A, const uint16_t* W, uint16_t* C, float* Cacc, int S, long long P,
+                   int rows_per_slot, int n_out, const int32_t* slot_offsets, const TileTable& t, hipStream_t st) {
   MfmaArgs g{};
   g.A = A;
   g.W = W;
   g.C = C;
+  g.Cacc = Cacc;
   g.P = (long long)S * rows_per_slot;
   g.w_rows = n_out;
   g.n_out = n_out;
@@ -320,7 +320,7 @@ int32_t gemm_wgrad(const uint16_t* A, const uint16_t* W, uint16_t* C, int S, lon
   g.slot_offsets = slot_offsets;
   g.k_rows = P;
   g.rows_per_slot = rows_per_slot;
-  return launch_mfma<EPI_NONE, MODE_TN>(g, st);
+  return Cacc ? launch_mfma<EPI_ACCUM, MODE_TN>(g, st) : launch_mfma<EPI_NONE, MODE_TN>(g, st);
 }
 
 // the generic path takes every valid shape whose 64-row tile count fits a grid dimension
@@ -430,10 +430,12 @@ extern "C" int32_t lz_route_backward(const float* dgates, const float* topk_gate
   return lz::launch_status();
 }
 
-extern "C" int32_t lz_ffn_backward(const void* dyp, const void* xp, const void* z, const void* h,
-                                   const int32_t* slot_offsets, const void* w1, const void* w2,
-                                   const lz_shape* shape, void* dxp, void* dw1, void* dw2, void* ws,
-                                   size_t ws_bytes, void* stream) {
+namespace {
+
+// dw1 / dw2 are bf16 gradients (accumulate == false: overwritten) or fp32 sums (accumulate == true: added to)
+int32_t ffn_backward(const void* dyp, const void* xp, const void* z, const void* h, const int32_t* slot_offsets,
+                     const void* w1, const void* w2, const lz_shape* shape, void* dxp, void* dw1, void* dw2,
+                     bool accumulate, void* ws, size_t ws_bytes, void* stream) {
   if (!train_shape(shape)) {
     GenericTrainWorkspace gw;
     const int32_t grc = check_train_generic(shape, ws, ws_bytes, &gw);
@@ -441,10 +443,10 @@ extern "C" int32_t lz_ffn_backward(const void* dyp, const void* xp, const void* 
     if (!dw1 || !dw2 || !slot_offsets) return LZ_EINVAL;
     if ((long long)shape->T * shape->k > 0 && (!dyp || !xp || !z || !h || !w1 || !w2 || !dxp)) return LZ_EINVAL;
     return shape->dtype == LZ_F32
-               ? generic_ffn_backward<float>(dyp, xp, z, h, slot_offsets, w1, w2, shape, dxp, dw1, dw2, gw,
-                                             (hipStream_t)stream)
-               : generic_ffn_backward<uint16_t>(dyp, xp, z, h, slot_offsets, w1, w2, shape, dxp, dw1, dw2, gw,
-                                                (hipStream_t)stream);
+               ? generic_ffn_backward<float>(dyp, xp, z, h, slot_offsets, w1, w2, shape, dxp, dw1, dw2, accumulate,
+                                             gw, (hipStream_t)stream)
+               : generic_ffn_backward<uint16_t>(dyp, xp, z, h, slot_offsets, w1, w2, shape, dxp, dw1, dw2,
+                                                accumulate, gw, (hipStream_t)stream);
   }
   TrainWorkspace w;
   const int32_t rc = check_train(shape, ws, ws_bytes, &w);
@@ -486,10 +488,28 @@ extern "C" int32_t lz_ffn_backward(const void* dyp, const void* xp, const void* 
     if ((r = gemm_nt(w.dz, (const uint16_t*)w1, (uint16_t*)dxp, P, n1, d, 1, t_rows, st)) != LZ_OK) return r;
   }
   // dW2[s] = H_s^T dyp_s  [ffn, d],   dW1[s] = xp_s^T dZ_s  [d, n1]
-  if ((r = gemm_wgrad((const uint16_t*)h, (const uint16_t*)dyp, (uint16_t*)dw2, S, P, ffn, d, slot_offsets, t_w2,
-                      st)) != LZ_OK)
+  if ((r = gemm_wgrad((const uint16_t*)h, (const uint16_t*)dyp, accumulate ? nullptr : (uint16_t*)dw2,
+                      accumulate ? (float*)dw2 : nullptr, S, P, ffn, d, slot_offsets, t_w2, st)) != LZ_OK)
     return r;
-  return gemm_wgrad((const uint16_t*)xp, w.dz, (uint16_t*)dw1, S, P, d, n1, slot_offsets, t_w1, st);
+  return gemm_wgrad((const uint16_t*)xp, w.dz, accumulate ? nullptr : (uint16_t*)dw1,
+                    accumulate ? (float*)dw1 : nullptr, S, P, d, n1, slot_offsets, t_w1, st);
+}
+
+}  // namespace
+
+extern "C" int32_t lz_ffn_backward(const void* dyp, const void* xp, const void* z, const void* h,
+                                   const int32_t* slot_offsets, const void* w1, const void* w2,
+                                   const lz_shape* shape, void* dxp, void* dw1, void* dw2, void* ws,
+                                   size_t ws_bytes, void* stream) {
+  return ffn_backward(dyp, xp, z, h, slot_offsets, w1, w2, shape, dxp, dw1, dw2, false, ws, ws_bytes, stream);
+}
+
+extern "C" int32_t lz_ffn_backward_accumulate(const void* dyp, const void* xp, const void* z, const void* h,
+                                              const int32_t* slot_offsets, const void* w1, const void* w2,
+                                              const lz_shape* shape, void* dxp, float* dw1_acc, float* dw2_acc,
+                                              void* ws, size_t ws_bytes, void* stream) {
+  return ffn_backward(dyp, xp, z, h, slot_offsets, w1, w2, shape, dxp, dw1_acc, dw2_acc, true, ws, ws_bytes,
+                      stream);
 }
 
 extern "C" int32_t lz_reduce_replica_grads(const void* dw_slot, const int32_t* slot_expert, int32_t S, int32_t E,

@@ -86,12 +86,14 @@ __global__ __launch_bounds__(256) void gemm_rows_generic_kernel(const Elem* __re
 }
 
 // Weight gradient of one slot per blockIdx.z: C[s][m, n] = sum over the slot's rows r of
-// A[r, m] * B[r, n]  (A [P, M], B [P, N], C [S, M, N]); an empty slot stores zeros.
+// A[r, m] * B[r, n]  (A [P, M], B [P, N], C [S, M, N]); an empty slot stores zeros.  With Cacc the
+// sum is added to that fp32 matrix instead (an empty slot adds nothing).
 template <typename Elem>
 __global__ __launch_bounds__(256) void gemm_wgrad_generic_kernel(const Elem* __restrict__ A, int M,
                                                                  const Elem* __restrict__ B, int N,
                                                                  const int32_t* __restrict__ slot_offsets,
-                                                                 long long P, Elem* __restrict__ C) {
+                                                                 long long P, Elem* __restrict__ C,
+                                                                 float* __restrict__ Cacc) {
   constexpr int TM = 64, TN = 64, TK = 16;
   __shared__ float sA[TK][TM + 1];
   __shared__ float sB[TK][TN + 1];
@@ -133,7 +135,9 @@ __global__ __launch_bounds__(256) void gemm_wgrad_generic_kernel(const Elem* __r
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       const int n = n0 + tx * 4 + j;
-      if (n < N) gstore<Elem>(C + ((size_t)s * M + m) * N + n, acc[i][j]);
+      if (n >= N) continue;
+      if (Cacc) Cacc[((size_t)s * M + m) * N + n] += acc[i][j];
+      else gstore<Elem>(C + ((size_t)s * M + m) * N + n, acc[i][j]);
     }
   }
 }
@@ -283,7 +287,8 @@ int32_t generic_forward_train(const void* xp, const int32_t* slot_offsets, const
 template <typename Elem>
 int32_t generic_ffn_backward(const void* dyp, const void* xp, const void* z, const void* h,
                              const int32_t* slot_offsets, const void* w1, const void* w2, const lz_shape* s,
-                             void* dxp, void* dw1, void* dw2, const GenericTrainWorkspace& w, hipStream_t st) {
+                             void* dxp, void* dw1, void* dw2, bool accumulate, const GenericTrainWorkspace& w,
+                             hipStream_t st) {
   const long long P = (long long)s->T * s->k;
   const int S = s->N * s->c, d = s->d, ffn = s->ffn, n1 = w.n1;
   if (P > 0) {
@@ -305,9 +310,11 @@ int32_t generic_ffn_backward(const void* dyp, const void* xp, const void* z, con
   }
   // dW2[s] = H_s^T dyp_s  [ffn, d],   dW1[s] = xp_s^T dZ_s  [d, n1]
   hipLaunchKernelGGL((gemm_wgrad_generic_kernel<Elem>), dim3((d + 63) / 64, (ffn + 63) / 64, S), dim3(256), 0, st,
-                     (const Elem*)h, ffn, (const Elem*)dyp, d, slot_offsets, P, (Elem*)dw2);
+                     (const Elem*)h, ffn, (const Elem*)dyp, d, slot_offsets, P, accumulate ? nullptr : (Elem*)dw2,
+                     accumulate ? (float*)dw2 : nullptr);
   hipLaunchKernelGGL((gemm_wgrad_generic_kernel<Elem>), dim3((n1 + 63) / 64, (d + 63) / 64, S), dim3(256), 0, st,
-                     (const Elem*)xp, d, (const Elem*)w.dz, n1, slot_offsets, P, (Elem*)dw1);
+                     (const Elem*)xp, d, (const Elem*)w.dz, n1, slot_offsets, P, accumulate ? nullptr : (Elem*)dw1,
+                     accumulate ? (float*)dw1 : nullptr);
   return lz::launch_status();
 }
 

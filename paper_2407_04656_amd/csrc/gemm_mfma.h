@@ -29,8 +29,10 @@ constexpr int kTileHeader = 64;  // ints before the tile arrays; [0] = number of
 constexpr int kGroupM = 4;       // row tiles of a work unit (same slot)
 constexpr int kGroupN = 8;       // column tiles of a work unit
 
-// *_KEEP: the training forward; besides act(z) the pre-activation z goes to MfmaArgs::Z
-enum { EPI_NONE = 0, EPI_GELU = 1, EPI_SWIGLU = 2, EPI_GELU_KEEP = 3, EPI_SWIGLU_KEEP = 4 };
+// *_KEEP: the training forward; besides act(z) the pre-activation z goes to MfmaArgs::Z.
+// EPI_ACCUM: the result is added to the fp32 matrix MfmaArgs::Cacc (weight gradients summed over
+// micro-batches) instead of being stored as bf16.
+enum { EPI_NONE = 0, EPI_GELU = 1, EPI_SWIGLU = 2, EPI_GELU_KEEP = 3, EPI_SWIGLU_KEEP = 4, EPI_ACCUM = 5 };
 
 struct TileTable {
   int32_t* header;
@@ -170,6 +172,7 @@ struct MfmaArgs {
   const uint16_t* A;    // MODE_NT, MODE_NN: [P, K];  MODE_TN: [k_rows, lda]
   const uint16_t* W;    // MODE_NT: [S, w_rows, K];  MODE_NN: [S, K, ldw];  MODE_TN: [k_rows, ldw]
   uint16_t* C;          // [P, n_out]
+  float* Cacc;          // EPI_ACCUM: [P, n_out] fp32, read, added to and written back
   long long P;          // rows of C (MODE_TN: S * rows_per_slot virtual rows)
   int K;                // contraction length (MODE_TN: per slot, from slot_offsets)
   int w_rows;           // MODE_NT: weight rows per slot
@@ -296,6 +299,9 @@ __device__ __forceinline__ void gemm_tile(const MfmaArgs& a, char* smem, int slo
   const uint16_t* tileW;
   uint32_t a_extent, w_extent;          // bytes the two descriptors cover
   int stepA = BK * 2, stepW = BK * 2;   // bytes one K step advances in each operand
+  // MODE_TN: a slot's rows of the k-major operands may cover more than 4 GiB, so the descriptors
+  // are rebuilt for every K step (base advanced by whole steps, extent = what is left of the slot)
+  [[maybe_unused]] unsigned long long a_bytes = 0, w_bytes = 0, stepA64 = 0, stepW64 = 0;
   if constexpr (MODE == MODE_TN) {
     // The descriptors start at the slot's first row and this tile's first column and end with
     // the slot's last row: the rows of the last, partial K step that belong to the next slot
@@ -306,10 +312,14 @@ __device__ __forceinline__ void gemm_tile(const MfmaArgs& a, char* smem, int slo
     const int m0 = row0 - slot * a.rows_per_slot;
     tileA = a.A + (size_t)s0 * a.lda + m0;
     tileW = a.W + (size_t)s0 * a.ldw + n0;
-    a_extent = K > 0 ? ((uint32_t)K * (uint32_t)a.lda - (uint32_t)m0) * 2u : 0u;
-    w_extent = K > 0 ? ((uint32_t)K * (uint32_t)a.ldw - (uint32_t)n0) * 2u : 0u;
-    stepA = 64 * a.lda * 2;
-    stepW = 64 * a.ldw * 2;
+    a_bytes = K > 0 ? ((unsigned long long)K * (unsigned)a.lda - (unsigned)m0) * 2ull : 0ull;
+    w_bytes = K > 0 ? ((unsigned long long)K * (unsigned)a.ldw - (unsigned)n0) * 2ull : 0ull;
+    stepA64 = 64ull * (unsigned)a.lda * 2ull;
+    stepW64 = 64ull * (unsigned)a.ldw * 2ull;
+    a_extent = a_bytes > 0xFFFFFFFFull ? 0xFFFFFFFFu : (uint32_t)a_bytes;  // (unused: see issue())
+    w_extent = w_bytes > 0xFFFFFFFFull ? 0xFFFFFFFFu : (uint32_t)w_bytes;
+    stepA = 0;
+    stepW = 0;
   } else if constexpr (MODE == MODE_NN) {
     if constexpr (GATHER) {
       tileA = a.A;  // the whole of x: a tile's rows lie anywhere in it (the host checked that it fits 32-bit offsets)
@@ -468,7 +478,15 @@ __device__ __forceinline__ void gemm_tile(const MfmaArgs& a, char* smem, int slo
     char* sX = smem + stage * kStageBytes;
     char* sW = sX + BM * kRowBytes;
     if constexpr (MODE != MODE_NT) {
-      const i32x4 wa = real ? wordsA : wordsNull, wb = real ? wordsB : wordsNull;
+      i32x4 wa = real ? wordsA : wordsNull, wb = real ? wordsB : wordsNull;
+      if constexpr (MODE == MODE_TN) {
+        const unsigned long long offA = (unsigned long long)(unsigned)step * stepA64;
+        const unsigned long long offW = (unsigned long long)(unsigned)step * stepW64;
+        const unsigned long long leftA = a_bytes > offA ? a_bytes - offA : 0ull;
+        const unsigned long long leftW = w_bytes > offW ? w_bytes - offW : 0ull;
+        wa = rsrc_words((const char*)tileA + offA, leftA > 0xFFFFFFFFull ? 0xFFFFFFFFu : (uint32_t)leftA);
+        wb = rsrc_words((const char*)tileW + offW, leftW > 0xFFFFFFFFull ? 0xFFFFFFFFu : (uint32_t)leftW);
+      }
       const uint32_t ldsX = lds0 + stage * kStageBytes, ldsW = ldsX + BM * kRowBytes;
 #pragma unroll
       for (int q = q0; q < q1; ++q) {
@@ -624,6 +642,46 @@ __device__ __forceinline__ void gemm_tile(const MfmaArgs& a, char* smem, int slo
   };
   auto rounded = [](float v) { return __uint_as_float(pack_bf16x2(v, 0.f) << 16); };  // the bf16 value that is stored
   const int out0 = n0 + wn * kWaveCols;
+  if constexpr (EPI == EPI_ACCUM) {
+    // fp32 read-modify-write: one 32 x 32 block at a time through the patch (128-byte rows), so that
+    // every row of the block is one whole line of the fp32 matrix
+    constexpr int kPitchF = 32 * 4 + 16;
+    char* const patchf = smem + wave * (32 * kPitchF);
+#pragma unroll
+    for (int j = 0; j < XF; ++j)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        char* const prow = patchf + (lane & 31) * kPitchF;
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const float4 v = {acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]};
+          *(float4*)(prow + (8 * g + 4 * half) * 4) = v;
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+          const int r = t * 8 + (lane >> 3), piece = lane & 7;
+          const float4 v = *(const float4*)(patchf + r * kPitchF + piece * 16);
+          const int row = row0 + wm * 32 * XF + j * 32 + r;
+          const int col = n0 + wn * 128 + i * 32 + piece * 4;  // row lengths are multiples of 8
+          if (row < row_end && col < a.n_out) {
+            float4* const dst = (float4*)(a.Cacc + (size_t)row * a.n_out + col);
+            float4 c = *dst;
+            c.x += v.x;
+            c.y += v.y;
+            c.z += v.z;
+            c.w += v.w;
+            *dst = c;
+          }
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+      }
+    return;
+  }
 #pragma unroll
   for (int j = 0; j < XF; ++j) {
     if constexpr (EPI == EPI_SWIGLU) {

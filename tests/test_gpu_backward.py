@@ -389,6 +389,120 @@ def test_backward_without_tokens_and_with_bad_offsets():
     assert not outs[0][2][1].any().item() and not outs[0][3][3].any().item()      # the empty slots
 
 
+@pytest.mark.parametrize("dtype,d,ffn,act", [("bf16", 256, 320, "gelu"), ("bf16", 512, 128, "swiglu"),
+                                             ("f32", 72, 200, "swiglu")])
+def test_weight_gradients_accumulate_in_fp32_over_micro_batches(dtype, d, ffn, act):
+    """Two micro-batches with different inputs and routing through backward_accumulate: the fp32
+    accumulators hold the sum of the two batches' slot gradients (an empty slot adds nothing), and
+    their per-expert reduction matches the fp64 oracle's sum of the two batches' expert gradients.
+    MFMA shapes (ragged K, n_out not a multiple of 256) and a generic fp32 shape."""
+    cfg = scaled(CONFIGS["c4_finegrained"], dtype=dtype, act=act, T=700, d=d, ffn=ffn, E=12, k=3, N=4, c=4)
+    bf16 = dtype == "bf16"
+    tol = 2e-2 if bf16 else 1e-5
+    w = expert_weights(cfg, threads=4)
+    shape = lz.Shape.from_config(cfg)
+    ids0, _ = om.route(step_inputs(cfg, 0)["logits"], cfg.k)
+    plan = oracle_plan(cfg, ids0)
+    layer = lz.MoELayer(shape, DEV)
+    layer.load_expert_weights(w["w1"], w["w2"], plan)
+    layer.enable_training()
+    layer.enable_accumulation()
+    rng = np.random.default_rng(33)
+    ref1 = ref2 = 0.0
+    for step in range(2):
+        inp = step_inputs(cfg, step)
+        layer.set_plan(plan, inp["rank_tok_off"])
+        ids, gates = om.route(inp["logits"], cfg.k)
+        disp = om.plan_dispatch(ids, inp["rank_tok_off"], plan, cfg.E, cfg.N, cfg.c)
+        dy = rng.standard_normal((cfg.T, cfg.d)).astype(np.float32)
+        dy = f32_to_bf16_bits(dy) if bf16 else dy
+        layer.forward_train(to_dev(inp["logits"]), to_dev(inp["x"], bf16))
+        layer.backward_accumulate(to_dev(dy, bf16))
+        torch.cuda.synchronize()
+        ref = ob.layer_backward(dy, inp["x"], ids, gates, disp["pair_to_row"], disp["row_to_pair"],
+                                disp["slot_offsets"], plan, w["w1"], w["w2"], act)
+        assert rel_err(to_host(layer.dx), ref["dx"]) <= tol
+        ref1 = ref1 + ref["dw1"].transpose(0, 2, 1)
+        ref2 = ref2 + ref["dw2"].transpose(0, 2, 1)
+    dw1, dw2 = layer.reduce_accumulated()
+    torch.cuda.synchronize()
+    assert rel_err(dw1.cpu().numpy(), ref1) <= tol
+    assert rel_err(dw2.cpu().numpy(), ref2) <= tol
+    # slot level: the accumulators of the slots of one expert add up to that expert's sum
+    acc1 = layer.dw1_acc.cpu().numpy().astype(np.float64)
+    for e in range(cfg.E):
+        slots = np.nonzero(plan == e)[0]
+        assert np.allclose(acc1[slots].sum(axis=0), dw1[e].cpu().numpy(), rtol=1e-5, atol=1e-6)
+
+
+def test_ffn_backward_slot_beyond_4_gib():
+    """Maximum sizes: one slot of 131 500 rows makes the k-major operands of the weight gradients
+    (dZ with 16 384 columns, h with 8 192) span 4.3 GB and 2.2 GB inside that slot, beyond 32-bit
+    byte offsets, and puts the slots after it more than 4 GiB into the buffers.  Checked on sampled
+    hidden columns (weight gradients) and sampled rows (data gradient) of the big slot and on the
+    small slot behind it, against the fp64 oracle."""
+    cfg = scaled(CONFIGS["c1_tiny"], act="swiglu", dtype="bf16", T=70000, k=2, d=256, ffn=8192, N=2, c=2)
+    counts = [3000, 131500, 0, 5500]
+    S, P, d, ffn = 4, cfg.T * cfg.k, cfg.d, cfg.ffn
+    n1 = 2 * ffn
+    assert sum(counts) == P and counts[1] * n1 * 2 > 2 ** 32
+    offsets = np.zeros(S + 1, dtype=np.int32)
+    offsets[1:] = np.cumsum(counts)
+    rng = np.random.default_rng(41)
+    slot_expert = np.array([3, 6, 1, 4], dtype=np.int32)
+    w = expert_weights(cfg, threads=8)
+    xph, dyph = _bf16(rng, (P, d)), _bf16(rng, (P, d), 0.5)
+    shape = lz.Shape.from_config(cfg)
+    bf = torch.bfloat16
+    w1, w2 = slot_weights(w, slot_expert, True)
+    nbytes = lz.lz_train_workspace_bytes(shape)
+    assert nbytes > 0
+    ws = torch.empty(nbytes, dtype=torch.uint8, device=DEV)
+    xp, dyp, off = to_dev(xph, True), to_dev(dyph, True), to_dev(offsets)
+    z = torch.empty((P, n1), dtype=bf, device=DEV)
+    h = torch.empty((P, ffn), dtype=bf, device=DEV)
+    yp = torch.empty((P, d), dtype=bf, device=DEV)
+    dxp = torch.empty((P, d), dtype=bf, device=DEV)
+    dw1 = torch.full((S, d, n1), 7.0, dtype=bf, device=DEV)
+    dw2 = torch.full((S, ffn, d), 7.0, dtype=bf, device=DEV)
+    print("slot beyond 4 GiB: forward_train", flush=True)
+    lz.lz_ffn_forward_train(xp, off, w1, w2, shape, z, h, yp, ws, nbytes)
+    torch.cuda.synchronize()
+    print("slot beyond 4 GiB: ffn_backward", flush=True)
+    lz.lz_ffn_backward(dyp, xp, z, h, off, w1, w2, shape, dxp, dw1, dw2, ws, nbytes)
+    torch.cuda.synchronize()
+    assert not dw1[2].any().item() and not dw2[2].any().item()          # the empty slot
+    Xp, dYp = om.widen(xph), om.widen(dyph)
+    F = np.array([0, 1, 257, 4095, 4096, 5000, 8190, 8191])
+    for s_ in (1, 3):
+        a_, b_ = int(offsets[s_]), int(offsets[s_ + 1])
+        e = int(slot_expert[s_])
+        W1, W2 = om.widen(w["w1"][e]), om.widen(w["w2"][e])                # [n1, d], [d, ffn]
+        X, dY = Xp[a_:b_], dYp[a_:b_]
+        Zs = np.concatenate([X @ W1[F].T, X @ W1[ffn + F].T], axis=1)     # gate columns, then up columns
+        dHs = dY @ W2[:, F]
+        dZs = ob.act_backward(dHs, Zs, "swiglu")
+        Hs = ob.act_forward(Zs, "swiglu")
+        cols = np.concatenate([F, ffn + F])
+        got1 = om.widen(to_host(dw1[s_][:, torch.from_numpy(cols).to(DEV)]))
+        ref1 = X.T @ dZs
+        assert np.max(np.abs(got1 - ref1)) <= TOL * np.max(np.abs(ref1)), s_
+        got2 = om.widen(to_host(dw2[s_][torch.from_numpy(F).to(DEV)]))
+        ref2 = Hs.T @ dY
+        assert np.max(np.abs(got2 - ref2)) <= TOL * np.max(np.abs(ref2)), s_
+        # stored intermediates at the sampled columns
+        zc = om.widen(to_host(z[a_:b_][:, torch.from_numpy(cols).to(DEV)]))
+        assert np.max(np.abs(zc - Zs)) <= TOL * np.max(np.abs(Zs)), s_
+        # data gradient and forward output on sampled rows (need the whole hidden width of a row)
+        rows = np.array([a_, a_ + 1, (a_ + b_) // 2, b_ - 2, b_ - 1])
+        Zr = Xp[rows] @ W1.T
+        dxp_ref = ob.act_backward(dYp[rows] @ W2, Zr, "swiglu") @ W1
+        yp_ref = ob.act_forward(Zr, "swiglu") @ W2.T
+        ridx = torch.from_numpy(rows).to(DEV)
+        assert rel_err(to_host(dxp[ridx]), dxp_ref) <= TOL, s_
+        assert rel_err(to_host(yp[ridx]), yp_ref) <= TOL, s_
+
+
 def _layer_backward_generic(cfg, tol):
     """Whole layer forward + backward through MoELayer on a shape the MFMA kernels do not serve."""
     inp = step_inputs(cfg)

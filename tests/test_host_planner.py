@@ -153,9 +153,11 @@ def test_training_calls_validate_arguments_without_a_gpu():
         with pytest.raises(lz.LzError) as ei:                        # no workspace
             lz.lz_ffn_backward(None, None, None, None, None, None, None, generic, None, None, None, None, 0, stream=0)
         assert ei.value.code == -3
-    # invalid, or beyond both paths (32-bit offsets into a slot's rows on the MFMA path, and too many
-    # 64-row tiles for the plain one)
-    for bad in (shape(k=9), shape(T=1 << 20, k=8, d=4096, ffn=14336)):
+    # activation tensors beyond 32-bit byte offsets are served too (the workspace is what it is)
+    assert lz.lz_train_workspace_bytes(shape(T=1 << 20, k=8, d=4096, ffn=14336)) > (1 << 36)
+    # invalid, or beyond both paths (one slot's weights past 32-bit offsets on the MFMA path and too
+    # many 64-row tiles for the plain one)
+    for bad in (shape(k=9), shape(T=1 << 23, k=2, d=264, ffn=128)):
         assert lz.lz_train_workspace_bytes(bad) == 0
         with pytest.raises(lz.LzError) as ei:
             lz.lz_ffn_backward(None, None, None, None, None, None, None, bad, None, None, None, None, 0, stream=0)
