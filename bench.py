@@ -30,6 +30,8 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 # HBM-side bytes per launch of the dominant kernel, from the rocprofv3 FETCH_SIZE / WRITE_SIZE passes
 # summarised in profiles/<workload>_hbm_traffic.md (counters cannot be read from inside this
 # process, so the figure is carried here and re-measured whenever the kernel changes).
+# c2_mixtral GEMM-1: FETCH_SIZE 6 798 961 KiB x 2.00 (what the counter reads for a plain copy of known
+# size) + WRITE_SIZE 459 402 KiB.
 MEASURED_TRAFFIC_BYTES = {"c2_mixtral": 14.39e9}
 
 NAMES = ["route", "plan", "permute", "ffn_up", "ffn_down", "combine"]
@@ -542,7 +544,12 @@ def main():
     wl = Workload(torch, lz, cfg, n_logits)
     wl.initial_plan()
     plan_note = wl.plan_note
-    if cfg.steps > 1:
+    rebalance_every = cfg.reshuffle_every if cfg.steps > 1 else 0
+    if rebalance_every:
+        plan_note = (f"Eq.1 + MRO recomputed from the step's routing at every popularity reshuffle (every "
+                     f"{rebalance_every} steps; lz_replan + lz_apply_transfers, untimed); fresh logits each step "
+                     f"({n_logits} draws)")
+    elif cfg.steps > 1:
         plan_note += f"; fresh logits each step ({n_logits} draws), plan kept"
     shape, layer = wl.shape, wl.layer
     bf16 = wl.bf16
@@ -555,8 +562,10 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    m = measure(wl, args.steps, args.warmup, fused_gather=args.fused_gather, cold=not args.no_extras)
-    ms_per_step = m["ms_per_step_wall"]
+    m = measure(wl, args.steps, args.warmup, rebalance_every=rebalance_every, fused_gather=args.fused_gather,
+                cold=not args.no_extras)
+    # with re-plans between steps the wall clock holds their pauses: the step time is the event-timed mean
+    ms_per_step = m["step_ms_by_events"]["mean"] if rebalance_every else m["ms_per_step_wall"]
     per = m["kernels_ms"]
     T, d, ffn, k = shape.T, shape.d, shape.ffn, shape.k
     tf_up = m["ffn_up_TFLOPs"]
@@ -603,6 +612,8 @@ def main():
             "input_gen_s": wl.gen_s,
         },
     }
+    if "rebalance" in m:
+        out["rebalance"] = m["rebalance"]
     if "permute_GBps_cold" in m:
         out["derived"]["permute_GBps_cold"] = m["permute_GBps_cold"]
         out["derived"]["combine_GBps_cold"] = m["combine_GBps_cold"]
