@@ -19,6 +19,7 @@
 // element sit in the same lane and register index.
 #pragma once
 #include "lz_common.h"
+#include <atomic>
 
 namespace {
 
@@ -764,22 +765,26 @@ __global__ __launch_bounds__(256, 1) void gemm_mfma_kernel(MfmaArgs a) {
 #endif
 }
 
+constexpr int kMaxDevices = 64;
+
 template <int EPI, int MODE = MODE_NT, bool GATHER = false>
 int32_t launch_mfma(const MfmaArgs& a, hipStream_t st) {
   static_assert(!GATHER || MODE == MODE_NN, "the gather is part of the forward's first GEMM only");
   void (*kern)(MfmaArgs) = gemm_mfma_kernel<EPI, MODE, GATHER>;
-  static bool configured = false;  // per-process attribute; idempotent, so a benign race at worst
-  static int n_workgroups = 0;
-  if (!configured) {
+  // per device: the LDS attribute is set and the CU count read on the first launch there (both
+  // idempotent, so two threads racing through the set-up do the same thing twice)
+  static std::atomic<int> workgroups_of_device[kMaxDevices];
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return LZ_EHIP;
+  int n_workgroups = workgroups_of_device[dev].load(std::memory_order_acquire);
+  if (n_workgroups == 0) {
     if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes) !=
         hipSuccess)
       return LZ_EHIP;
-    int dev = 0, cus = 0;
-    if (hipGetDevice(&dev) != hipSuccess ||
-        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
-      return LZ_EHIP;
+    int cus = 0;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return LZ_EHIP;
     n_workgroups = cus >= 8 ? cus / 8 * 8 : 8;  // one per CU (the LDS a workgroup takes allows no more)
-    configured = true;
+    workgroups_of_device[dev].store(n_workgroups, std::memory_order_release);
   }
   hipLaunchKernelGGL(kern, dim3(n_workgroups), dim3(256), kLdsBytes, st, a);
   return lz::launch_status();
