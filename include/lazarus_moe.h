@@ -367,6 +367,16 @@ int32_t lz_apply_transfers(const lz_transfer* xfers, int32_t n,
                            void* w1_new, void* w2_new, int32_t S_new,
                            const lz_shape* shape, void* stream);
 
+/* ---- diagnostics ------------------------------------------------------------------------- */
+
+/* Records, for a launch shaped like the grouped GEMM's persistent kernel (256 threads and the
+ * same LDS per workgroup, so one workgroup per CU), the id (0..7) of the XCD that each workgroup
+ * ran on, read from the hardware's XCC_ID register.  The GEMM gives workgroup b the home queue
+ * b % 8 on the expectation that consecutive workgroups go to consecutive XCDs; this call lets a
+ * test or a user check that expectation on their machine (only cache locality depends on it).
+ *   xcc_of_workgroup  dev [n_workgroups] i32 (out);  0 <= n_workgroups <= 65535 */
+int32_t lz_debug_xcc_ids(int32_t* xcc_of_workgroup, int32_t n_workgroups, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

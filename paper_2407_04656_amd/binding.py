@@ -15,7 +15,7 @@ __all__ = [
     "lz_replan", "lz_apply_transfers", "MoELayer",
     "lz_pack_weights", "lz_train_workspace_bytes", "lz_ffn_forward_train", "lz_combine_backward",
     "lz_ffn_backward", "lz_ffn_backward_accumulate", "lz_permute_backward", "lz_route_backward", "lz_reduce_replica_grads",
-    "lz_reduce_replica_grads_dtype",
+    "lz_reduce_replica_grads_dtype", "lz_debug_xcc_ids",
 ]
 
 LZ_F32, LZ_BF16 = 0, 1
@@ -126,6 +126,7 @@ def _load():
         "lz_route_backward": (i32, [vp, vp, vp, sp, vp, vp]),
         "lz_reduce_replica_grads": (i32, [vp, vp, i32, i32, C.c_int64, vp, vp]),
         "lz_reduce_replica_grads_dtype": (i32, [vp, vp, i32, i32, C.c_int64, i32, vp, vp]),
+        "lz_debug_xcc_ids": (i32, [vp, i32, vp]),
     }
     for name, (res, args) in sig.items():
         fn = getattr(L, name)
@@ -298,6 +299,11 @@ def lz_reduce_replica_grads_dtype(dw_slot, slot_expert, S, E, elems_per_slot, dt
     _check(lib.lz_reduce_replica_grads_dtype(_ptr(dw_slot), _ptr(slot_expert), S, E, elems_per_slot, dtype, _ptr(dw),
                                              _stream() if stream is None else stream),
            "lz_reduce_replica_grads_dtype")
+
+
+def lz_debug_xcc_ids(xcc_of_workgroup, n_workgroups, stream=None):
+    _check(lib.lz_debug_xcc_ids(_ptr(xcc_of_workgroup), n_workgroups, _stream() if stream is None else stream),
+           "lz_debug_xcc_ids")
 
 
 # ------------------------------------------------------------------ host planning

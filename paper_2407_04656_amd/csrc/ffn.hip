@@ -322,3 +322,28 @@ extern "C" int32_t lz_expert_ffn_gather(const void* x, const int32_t* row_to_pai
   if (rc != LZ_OK) return rc;
   return lz_ffn_down(w2, shape, yp, ws, ws_bytes, stream);
 }
+
+// ------------------------------------------------------------------------------------------
+// Diagnostic: which XCD does the hardware give the workgroups of a launch shaped like the
+// persistent GEMM's (256 threads, the same dynamic LDS, hence one workgroup per CU)?
+// ------------------------------------------------------------------------------------------
+namespace {
+__global__ __launch_bounds__(256, 1) void xcc_ids_kernel(int32_t* __restrict__ out) {
+  extern __shared__ __attribute__((aligned(1024))) char smem_probe[];
+  uint32_t id;
+  asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(id));
+  if (threadIdx.x == 0) out[blockIdx.x] = (int32_t)(id & 0xFu);
+}
+}  // namespace
+
+extern "C" int32_t lz_debug_xcc_ids(int32_t* xcc_of_workgroup, int32_t n_workgroups, void* stream) {
+  if (n_workgroups < 0 || n_workgroups > 65535) return LZ_EINVAL;
+  if (n_workgroups == 0) return LZ_OK;
+  if (!xcc_of_workgroup) return LZ_EINVAL;
+  if (hipFuncSetAttribute((const void*)xcc_ids_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes) !=
+      hipSuccess)
+    return LZ_EHIP;
+  hipLaunchKernelGGL(xcc_ids_kernel, dim3(n_workgroups), dim3(256), kLdsBytes, (hipStream_t)stream,
+                     xcc_of_workgroup);
+  return lz::launch_status();
+}
