@@ -309,6 +309,29 @@ def measure(wl, steps, warmup, rebalance_every=0, fused_gather=False, cold=False
     return out
 
 
+def graph_replay_ms(wl, n=100):
+    """The same step captured once in a HIP graph and replayed: what a launch-bound shape gains when
+    the caller records the library's calls (they neither allocate nor synchronise) instead of
+    issuing them one by one."""
+    torch = wl.torch
+    wl.step(wl.logits_all[0])
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    stream = torch.cuda.Stream()
+    stream.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.graph(graph, stream=stream):
+        wl.step(wl.logits_all[0])
+    torch.cuda.synchronize()
+    for _ in range(5):
+        graph.replay()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(n):
+        graph.replay()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) * 1e3 / n
+
+
 def compact(cfg, m, plan_note):
     """The figures of one workload for the `workloads` object."""
     T = cfg.T
@@ -356,6 +379,10 @@ def other_workloads(torch, lz, skip):
             m = measure(wl, steps, warmup)
             note = wl.plan_note + ("; fresh logits each step, plan kept" if cfg.steps > 1 else "")
             res[name] = compact(cfg, m, note)
+            if name in ("c1_tiny", "c4_finegrained"):   # the shapes with the most launches per unit of work
+                g = graph_replay_ms(wl)
+                res[name]["hip_graph_replay"] = {"ms_per_step": g, "tokens_per_s": cfg.T / (g * 1e-3),
+                                                 "note": "the step's launches captured once and replayed (wall clock over 100 replays)"}
         del wl
         torch.cuda.empty_cache()
     return res
@@ -626,6 +653,10 @@ def main():
                 "permute_ms_unfused": per["permute"],
                 "note": "same step with the reshuffle done by the first GEMM's activation loads "
                         "(lz_ffn_up_gather reads x through row_to_pair; no permute kernel, no xp buffer)"}
+        g_ms = graph_replay_ms(wl, 50)
+        out["hip_graph_replay"] = {"ms_per_step": g_ms, "tokens_per_s": T / (g_ms * 1e-3),
+                                   "note": "the step's launches captured once in a HIP graph and replayed, no event "
+                                           "records between the kernels (wall clock over 50 replays); not `value`"}
         if bf16:
             out["training"] = training_pass(torch, lz, layer, cfg, wl.logits_all[0], wl.x)
     host_inp, host_w = wl.inp, wl.w
