@@ -57,6 +57,8 @@ __global__ __launch_bounds__(256) void permute_elem_kernel(const Elem* __restric
 // Token-major form of the same reshuffle: xp[pair_to_row[t*k+kk], :] = x[t, :] for every pair.
 // Each row of x is read once and written k times, which is exactly the compulsory traffic
 // (the row-major gather above re-reads x once per copy when the copies land on different XCDs).
+// U lane-vectors of the row are loaded before the first is stored.
+template <int U>
 __global__ __launch_bounds__(256) void permute_scatter_kernel(const u32x4* __restrict__ x,
                                                               const int32_t* __restrict__ pair_to_row,
                                                               int T, int k, long long P, int vec_per_row,
@@ -75,18 +77,16 @@ __global__ __launch_bounds__(256) void permute_scatter_kernel(const u32x4* __res
   }
   const u32x4* src = x + (size_t)t * vec_per_row;
   int v = lane;
-  for (; v + 3 * lz::kWave < vec_per_row; v += 4 * lz::kWave) {
-    const u32x4 a = __builtin_nontemporal_load(src + v), b = __builtin_nontemporal_load(src + v + lz::kWave),
-                c = __builtin_nontemporal_load(src + v + 2 * lz::kWave),
-                d = __builtin_nontemporal_load(src + v + 3 * lz::kWave);
+  for (; v + (U - 1) * lz::kWave < vec_per_row; v += U * lz::kWave) {
+    u32x4 in[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) in[u] = __builtin_nontemporal_load(src + v + u * lz::kWave);
 #pragma unroll
     for (int kk = 0; kk < lz::kMaxK; ++kk)
       if (kk < k && rows[kk] >= 0) {
         u32x4* dst = xp + (size_t)rows[kk] * vec_per_row + v;
-        __builtin_nontemporal_store(a, dst);
-        __builtin_nontemporal_store(b, dst + lz::kWave);
-        __builtin_nontemporal_store(c, dst + 2 * lz::kWave);
-        __builtin_nontemporal_store(d, dst + 3 * lz::kWave);
+#pragma unroll
+        for (int u = 0; u < U; ++u) __builtin_nontemporal_store(in[u], dst + u * lz::kWave);
       }
   }
   for (; v < vec_per_row; v += lz::kWave) {
@@ -122,42 +122,60 @@ __device__ __forceinline__ void fma8(float* acc, const u32x4& v, float g) {
 }
 
 // y[t, :] = sum_kk gate[t, kk] * yp[pair_to_row[t*k+kk], :]   bf16, 8 elements per lane-vector
-// (gates == nullptr: all gates 1, the backward of the reshuffle)
+// (gates == nullptr: all gates 1, the backward of the reshuffle).  K = top-k (compile time, so the
+// row indices and loaded vectors stay in registers); U lane-vectors of every row are loaded before
+// the first is used, K * U 16-byte loads in flight per lane.
+template <int K, int U>
 __global__ __launch_bounds__(256) void combine_bf16_kernel(const u32x4* __restrict__ yp,
                                                            const int32_t* __restrict__ pair_to_row,
                                                            const float* __restrict__ gates, int T,
-                                                           int k, long long P, int vec_per_row,
+                                                           long long P, int vec_per_row,
                                                            u32x4* __restrict__ y) {
   const int lane = threadIdx.x % lz::kWave;
   const long long t = (long long)blockIdx.x * kRowsPerBlock + threadIdx.x / lz::kWave;
   if (t >= T) return;
-  int rows[lz::kMaxK];
-  float g[lz::kMaxK];
+  const u32x4* src[K];
+  float g[K];
+  bool ok[K];  // a pair without a row adds nothing (the same for the whole wave: no divergence)
 #pragma unroll
-  for (int kk = 0; kk < lz::kMaxK; ++kk) {
-    rows[kk] = -1;
-    g[kk] = 0.f;
-    if (kk < k) {
-      const int r = pair_to_row[t * k + kk];
-      rows[kk] = (r >= 0 && r < P) ? r : -1;
-      g[kk] = gates ? gates[t * k + kk] : 1.f;
-    }
+  for (int kk = 0; kk < K; ++kk) {
+    const int r = pair_to_row[t * K + kk];
+    ok[kk] = r >= 0 && r < P;
+    src[kk] = yp + (size_t)(ok[kk] ? r : 0) * vec_per_row;
+    g[kk] = gates ? gates[t * K + kk] : 1.f;
   }
-  for (int v = lane; v < vec_per_row; v += lz::kWave) {
-    u32x4 in[lz::kMaxK];
-#pragma unroll
-    for (int kk = 0; kk < lz::kMaxK; ++kk)
-      if (kk < k && rows[kk] >= 0) in[kk] = __builtin_nontemporal_load(yp + (size_t)rows[kk] * vec_per_row + v);
-    float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int kk = 0; kk < lz::kMaxK; ++kk)
-      if (kk < k && rows[kk] >= 0) fma8(acc, in[kk], g[kk]);
+  auto pack = [](const float* acc) {
     u32x4 out;
     out.x = uint32_t(lz::f32_to_bf16(acc[0])) | (uint32_t(lz::f32_to_bf16(acc[1])) << 16);
     out.y = uint32_t(lz::f32_to_bf16(acc[2])) | (uint32_t(lz::f32_to_bf16(acc[3])) << 16);
     out.z = uint32_t(lz::f32_to_bf16(acc[4])) | (uint32_t(lz::f32_to_bf16(acc[5])) << 16);
     out.w = uint32_t(lz::f32_to_bf16(acc[6])) | (uint32_t(lz::f32_to_bf16(acc[7])) << 16);
-    y[(size_t)t * vec_per_row + v] = out;
+    return out;
+  };
+  u32x4* const dst = y + (size_t)t * vec_per_row;
+  int v = lane;
+  for (; v + (U - 1) * lz::kWave < vec_per_row; v += U * lz::kWave) {
+    u32x4 in[U][K];
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+#pragma unroll
+      for (int kk = 0; kk < K; ++kk)
+        if (ok[kk]) in[u][kk] = __builtin_nontemporal_load(src[kk] + v + u * lz::kWave);
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int kk = 0; kk < K; ++kk)
+        if (ok[kk]) fma8(acc, in[u][kk], g[kk]);
+      dst[v + u * lz::kWave] = pack(acc);
+    }
+  }
+  for (; v < vec_per_row; v += lz::kWave) {
+    float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int kk = 0; kk < K; ++kk)
+      if (ok[kk]) fma8(acc, __builtin_nontemporal_load(src[kk] + v), g[kk]);
+    dst[v] = pack(acc);
   }
 }
 
@@ -222,7 +240,7 @@ extern "C" int32_t lz_permute_scatter(const void* x, const int32_t* pair_to_row,
   const size_t row_bytes = (size_t)shape->d * lz::elem_bytes(shape->dtype);
   const unsigned blocks = unsigned((shape->T + kRowsPerBlock - 1) / kRowsPerBlock);
   if (row_bytes % 16 == 0 && aligned16(x) && aligned16(xp)) {
-    hipLaunchKernelGGL(permute_scatter_kernel, dim3(blocks), dim3(256), 0, st, (const u32x4*)x, pair_to_row,
+    hipLaunchKernelGGL(permute_scatter_kernel<4>, dim3(blocks), dim3(256), 0, st, (const u32x4*)x, pair_to_row,
                        shape->T, shape->k, P, int(row_bytes / 16), (u32x4*)xp);
   } else if (shape->dtype == LZ_F32) {
     hipLaunchKernelGGL(permute_scatter_elem_kernel<float>, dim3(blocks), dim3(256), 0, st, (const float*)x,
@@ -242,8 +260,34 @@ int32_t combine(const void* yp, const int32_t* pair_to_row, const float* topk_ga
   const long long P = (long long)shape->T * shape->k;
   const unsigned blocks = unsigned((shape->T + kRowsPerBlock - 1) / kRowsPerBlock);
   if (shape->dtype == LZ_BF16 && shape->d % 8 == 0 && aligned16(yp) && aligned16(y)) {
-    hipLaunchKernelGGL(combine_bf16_kernel, dim3(blocks), dim3(256), 0, st, (const u32x4*)yp,
-                       pair_to_row, topk_gates, shape->T, shape->k, P, shape->d / 8, (u32x4*)y);
+    const u32x4* src = (const u32x4*)yp;
+    u32x4* dst = (u32x4*)y;
+    const int T = shape->T, vec = shape->d / 8;
+    // lane-vectors of a row loaded ahead: 4 (measured: 5.7 TB/s against 5.2 with one; 8 is no
+    // faster), fewer only for rows shorter than that
+    const int ahead = vec >= 4 * lz::kWave ? 4 : (vec >= 2 * lz::kWave ? 2 : 1);
+#define LZ_COMBINE_U(K, U)                                                                                    \
+  hipLaunchKernelGGL((combine_bf16_kernel<K, U>), dim3(blocks), dim3(256), 0, st, src, pair_to_row, topk_gates, \
+                     T, P, vec, dst)
+#define LZ_COMBINE(K)                       \
+  case K:                                   \
+    if (ahead == 4) LZ_COMBINE_U(K, 4);     \
+    else if (ahead == 2) LZ_COMBINE_U(K, 2); \
+    else LZ_COMBINE_U(K, 1);                \
+    break
+    switch (shape->k) {  // 1 <= k <= kMaxK = 8, checked by shape_ok
+      LZ_COMBINE(1);
+      LZ_COMBINE(2);
+      LZ_COMBINE(3);
+      LZ_COMBINE(4);
+      LZ_COMBINE(5);
+      LZ_COMBINE(6);
+      LZ_COMBINE(7);
+      LZ_COMBINE(8);
+      default: return LZ_ESHAPE;
+    }
+#undef LZ_COMBINE
+#undef LZ_COMBINE_U
   } else if (shape->dtype == LZ_BF16) {
     hipLaunchKernelGGL(combine_elem_kernel<true>, dim3(blocks), dim3(256), 0, st, yp, pair_to_row,
                        topk_gates, shape->T, shape->k, P, shape->d, y);
