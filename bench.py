@@ -332,6 +332,37 @@ def graph_replay_ms(wl, n=100):
     return (time.perf_counter() - t0) * 1e3 / n
 
 
+def compare_fused_gather(wl, rounds=4, steps=8):
+    """The step with the permute kernel against the step whose first GEMM reads x through the row map
+    (lz_ffn_up_gather), in the same process and interleaved (boxes and minutes differ by more than
+    the two paths do): `rounds` alternating blocks of `steps` event-timed steps each."""
+    torch = wl.torch
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+    acc = {False: [], True: []}
+    for fused in (False, True):
+        for _ in range(3):
+            wl.step(wl.logits_all[0], fused_gather=fused)
+    torch.cuda.synchronize()
+    for _ in range(rounds):
+        for fused in (False, True):
+            marks = [[ev() for _ in range(7)] for _ in range(steps)]
+            wl.step(wl.logits_all[0], fused_gather=fused)        # untimed: the switch itself
+            for m in marks:
+                wl.step(wl.logits_all[0], m, fused_gather=fused)
+            torch.cuda.synchronize()
+            acc[fused] += [[m[i].elapsed_time(m[i + 1]) for i in range(6)] + [m[0].elapsed_time(m[6])] for m in marks]
+    mean = {f: np.mean(np.array(v), axis=0) for f, v in acc.items()}
+    col = {n: i for i, n in enumerate(NAMES + ["step"])}
+    return {"ms_per_step": float(mean[True][col["step"]]), "ms_per_step_unfused": float(mean[False][col["step"]]),
+            "ffn_up_ms": float(mean[True][col["ffn_up"]]), "ffn_up_ms_unfused": float(mean[False][col["ffn_up"]]),
+            "ffn_down_ms": float(mean[True][col["ffn_down"]]), "ffn_down_ms_unfused": float(mean[False][col["ffn_down"]]),
+            "permute_ms_unfused": float(mean[False][col["permute"]]),
+            "steps_each": rounds * steps,
+            "note": "same step with the reshuffle done by the first GEMM's activation loads (lz_ffn_up_gather reads x "
+                    "through row_to_pair; no permute kernel, no xp buffer); the two paths measured in alternating "
+                    "blocks of the same process"}
+
+
 def compact(cfg, m, plan_note):
     """The figures of one workload for the `workloads` object."""
     T = cfg.T
@@ -379,6 +410,8 @@ def other_workloads(torch, lz, skip):
             m = measure(wl, steps, warmup)
             note = wl.plan_note + ("; fresh logits each step, plan kept" if cfg.steps > 1 else "")
             res[name] = compact(cfg, m, note)
+            if name == "c4_finegrained":                # top-6: the reshuffle moves the most bytes per flop here
+                res[name]["fused_gather"] = compare_fused_gather(wl)
             if name in ("c1_tiny", "c4_finegrained"):   # the shapes with the most launches per unit of work
                 g = graph_replay_ms(wl)
                 res[name]["hip_graph_replay"] = {"ms_per_step": g, "tokens_per_s": cfg.T / (g * 1e-3),
@@ -645,14 +678,8 @@ def main():
         out["derived"]["permute_GBps_cold"] = m["permute_GBps_cold"]
         out["derived"]["combine_GBps_cold"] = m["combine_GBps_cold"]
     if not args.no_extras:
-        if bf16 and hasattr(lz, "lz_ffn_up_gather") and not args.fused_gather:
-            g = measure(wl, max(5, args.steps // 2), 2, fused_gather=True)
-            out["fused_gather"] = {
-                "ms_per_step": g["step_ms_by_events"]["mean"], "ms_per_step_unfused": m["step_ms_by_events"]["mean"],
-                "ffn_up_ms": g["kernels_ms"]["ffn_up"], "ffn_up_ms_unfused": per["ffn_up"],
-                "permute_ms_unfused": per["permute"],
-                "note": "same step with the reshuffle done by the first GEMM's activation loads "
-                        "(lz_ffn_up_gather reads x through row_to_pair; no permute kernel, no xp buffer)"}
+        if bf16 and not args.fused_gather:
+            out["fused_gather"] = compare_fused_gather(wl)
         g_ms = graph_replay_ms(wl, 50)
         out["hip_graph_replay"] = {"ms_per_step": g_ms, "tokens_per_s": T / (g_ms * 1e-3),
                                    "note": "the step's launches captured once in a HIP graph and replayed, no event "
