@@ -4,8 +4,8 @@
 //   C[rows of a slot, n] = epi( sum_k A(row, k) * W[slot](n, k) )
 //
 // Persistent kernel, one workgroup per CU, drawing 256x256 tiles from its XCD's queue.  4 waves
-// in 2x2, each wave a 128x128 patch = 4x4 v_mfma_f32_32x32x16_bf16 accumulators (fp32, 256
-// AGPRs).  Operand tiles are streamed HBM -> LDS with 16-byte buffer loads that write LDS
+// in 2x2, each wave a 128x128 patch = 8x8 v_mfma_f32_16x16x32_bf16 accumulators (fp32, 256
+// AGPRs; this shape sustains 15 % more flops under the chip's power cap than 32x32x16).  Operand tiles are streamed HBM -> LDS with 16-byte buffer loads that write LDS
 // directly, through two LDS stages of 64 k; fragment reads are software pipelined over two
 // register sets.  An operand may be k-contiguous ([row, k]: 256 tile rows of 128 B, read with
 // ds_read_b128) or k-major ([k, column]: 64 k-rows of 512 B, read with the transposing
@@ -16,7 +16,7 @@
 // with 4 consecutive output columns per accumulator group; the epilogue regroups them through
 // a per-wave LDS patch into whole 128-byte lines.  For SwiGLU the weight tile interleaves
 // 32-wide fragments of the gate and the up projection, so the gate and up values of one output
-// element sit in the same lane and register index.
+// element sit in the same lane and register index of two accumulators.
 #pragma once
 #include "lz_common.h"
 #include <atomic>
@@ -24,7 +24,7 @@
 namespace {
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
-typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
 
 constexpr int kTileHeader = 64;  // ints before the tile arrays; [0] = number of row tiles
 constexpr int kGroupM = 4;       // row tiles of a work unit (same slot)
@@ -261,19 +261,13 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
 // the key row/2.
 __device__ __forceinline__ int swz(int row) { return (row >> 1) & 7; }
 
-// Scheduling hint for one 16-wide K slice of NM MFMAs: the ND ds_reads go out one per MFMA from
-// the start of the slice (the next slice waits on them), the NV direct-to-LDS loads are spread
-// evenly over the slice.
-template <int Q, int ND, int NM, int NV>
-__device__ __forceinline__ void sched_slice() {
-  if constexpr (Q < NM) {
-    constexpr int v = (NV * (Q + 1)) / NM - (NV * Q) / NM;
-    if constexpr (v > 0) __builtin_amdgcn_sched_group_barrier(0x020, v, 0);       // VMEM read
-    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                             // MFMA
-    if constexpr (Q < ND) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);      // DS read
-    sched_slice<Q + 1, ND, NM, NV>();
-  }
-}
+// 16-byte piece p (8 columns) of k-row kr of a k-major tile lives at piece position p ^ swz_kmajor(kr)
+// of its 512-byte LDS row.  A transposing read is served 32 lanes at a time: two lane groups, each
+// touching 4 consecutive k-rows (kr % 4 = 0..3) at the same 32 bytes (one 16-column fragment), the
+// two groups 8 k-rows apart.  Bits 2-3 of the key move the four k-rows of a group into four
+// different quarters of the banks, bit 1 moves the second group's fragments 32 bytes on, so the
+// eight 32-byte runs fall into eight different bank groups.
+__device__ __forceinline__ int swz_kmajor(int kr) { return ((kr & 3) << 2) | (((kr >> 3) & 1) << 1); }
 
 // One output tile of 64*XF rows x 256 columns n of the weight operand W(n, k) ("weight rows"
 // below, whichever way W lies in memory).  XF = 32-row activation fragments per wave: the 2x2 waves each own (32*XF) x 128 of the tile, so a slot's ragged last tile costs
@@ -282,7 +276,7 @@ template <int EPI, int XF, int MODE, bool GATHER>
 __device__ __forceinline__ void gemm_tile(const MfmaArgs& a, char* smem, int slot, int row0, int row_end, int n0) {
   constexpr bool TA = MODE == MODE_TN, TB = MODE != MODE_NT;  // k-major left / right operand
   constexpr bool kGated = EPI == EPI_SWIGLU || EPI == EPI_SWIGLU_KEEP;
-  constexpr int KS = BK / 16;             // 16-wide MFMA slices per stage
+  constexpr int KS = BK / 32;             // 32-wide MFMA slices per stage
   constexpr int kLoadsX = TA ? 8 : 2 * XF;  // 1-KiB wave loads per wave for the left tile (8 rows, or 2 k-rows, each)
   constexpr int kLoadsW = 8;              // ... for the 256-row weight tile
   // The empty asm keeps the per-lane address arithmetic below inside the tile: hoisted out of
@@ -352,11 +346,10 @@ __device__ __forceinline__ void gemm_tile(const MfmaArgs& a, char* smem, int slo
   // because a direct-to-LDS load fixes the LDS side to lane order).
   //
   // k-major operand: load u fills two k-rows of 512 B, lane l landing at k-row 2u + l/32, 16-byte
-  // piece l%32, which must hold logical piece (l%32) ^ 4*(k-row % 4): the four k-rows that one
-  // transposing read touches at the same columns then lie in four different quarters of the banks.
+  // piece l%32, which must hold logical piece (l%32) ^ swz_kmajor(k-row).
   auto voff_kmajor = [&](int i, int ld, int col0) {
     const int kr = (wave * 8 + i) * 2 + (lane >> 5);
-    const int piece = (lane & 31) ^ ((kr & 3) << 2);
+    const int piece = (lane & 31) ^ swz_kmajor(kr);
     return (int)(((uint32_t)kr * (uint32_t)ld + (uint32_t)col0 + (uint32_t)piece * 8u) * 2u);
   };
   int voffX[kLoadsX], voffW[kLoadsW];
@@ -391,7 +384,7 @@ __device__ __forceinline__ void gemm_tile(const MfmaArgs& a, char* smem, int slo
     if constexpr (TB && kGated) {
       // k-major SwiGLU weights [K, 2 ffn]: 32-column fragments alternate gate and up columns
       const int kr = (wave * 8 + i) * 2 + (lane >> 5);
-      const int piece = (lane & 31) ^ ((kr & 3) << 2);
+      const int piece = (lane & 31) ^ swz_kmajor(kr);
       const int f = piece >> 2;
       const int col = n0 + (f >> 1) * 32 + (piece & 3) * 8 + ((f & 1) ? a.up_row0 : 0);
       voffW[i] = (int)(((uint32_t)kr * (uint32_t)a.ldw + (uint32_t)col) * 2u);
@@ -411,64 +404,66 @@ __device__ __forceinline__ void gemm_tile(const MfmaArgs& a, char* smem, int slo
     }
   }
 
-  // ---- fragment read addresses: lane l reads row (l%32) of a 32-row fragment, logical chunk
-  // 2*ks + l/32 of the stage's K slice
+  // ---- fragment read addresses.  A fragment is 16 rows (of the activation tile, or weight rows) x
+  // the 32 k of a slice; lane l holds row l%16, the 8 consecutive k of chunk l/16 (the operand
+  // layout of v_mfma_f32_16x16x32_bf16).  k-contiguous tile: one ds_read_b128 at row l%16, logical
+  // chunk 4*slice + l/16 of the stage's 8.
+  constexpr int NA = 2 * XF;  // activation fragments per wave (16 rows each)
+  constexpr int NW = 8;       // weight fragments per wave (16 weight rows each)
   int fragoff[KS];
   {
-    const int r = lane & 31;
+    const int r = lane & 15;
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) fragoff[ks] = r * kRowBytes + (((ks * 2 + (lane >> 5)) ^ swz(r)) << 4);
+    for (int ks = 0; ks < KS; ++ks) fragoff[ks] = r * kRowBytes + (((ks * 4 + (lane >> 4)) ^ swz(r)) << 4);
   }
   const int xbase = wm * 32 * XF * kRowBytes;               // this wave's activation rows
   const int wbase = BM * kRowBytes + wn * 128 * kRowBytes;  // this wave's 128 weight rows
-  // k-major tiles: lane 16g + s supplies the address of k-row 8*(g/2) + s/4 (of the 16-wide
-  // slice), column quad s%4 of the group's 16 columns (16*(g%2) into the 32-column fragment)
-  int tfoX[XF], tfoW[4];
+  // k-major tiles: lane 16g + q supplies the address of k-row 8g + q/4 of the 32-wide slice, column
+  // quad q%4 of the fragment's 16 columns; the transposing read hands lane 16g + i column i at those
+  // four k-rows, a second read 4 k-rows on completes the lane's 8 consecutive k.
+  int tfo[2];  // byte offset inside a stage's k-major tile for fragment 0 (and its second piece position), slice 0
   {
-    const int g = lane >> 4, s = lane & 15;
-    const int part = (8 * (g >> 1) + (s >> 2)) * 512 + ((2 * (g & 1) + ((s >> 1) & 1)) << 4) + ((s & 1) << 3);
-#pragma unroll
-    for (int j = 0; j < XF; ++j) tfoX[j] = part + 64 * ((XF * wm + j) ^ (s >> 2));
-#pragma unroll
-    for (int i = 0; i < 4; ++i) tfoW[i] = BM * kRowBytes + part + 64 * ((4 * wn + i) ^ (s >> 2));
+    const int g = lane >> 4, q = lane & 15;
+    const int kr = 8 * g + (q >> 2);
+    // fragment f = pieces 2f, 2f+1 of the k-row; the swizzle key (even) is added by XOR per fragment below
+    tfo[0] = kr * 512 + ((q & 1) << 3) + (((q >> 1) & 1) << 4);
+    tfo[1] = swz_kmajor(kr);
   }
+  auto kmajor_addr = [&](int frag16) {  // fragment frag16 (0..15) of the 256-column tile, slice 0
+    return tfo[0] + ((((frag16 << 1) ^ tfo[1]) & 31) << 4);
+  };
   auto read_kmajor = [&](const char* p) {
     const i16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) i16x4*)p);
     const i16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) i16x4*)(p + 4 * 512));
     return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
   };
   auto frag_x = [&](const char* stage, int ks, int j) {
-    if constexpr (TA) return read_kmajor(stage + ks * 16 * 512 + tfoX[j]);
-    else return *(const bf16x8*)(stage + xbase + j * 32 * kRowBytes + fragoff[ks]);
+    if constexpr (TA) return read_kmajor(stage + ks * 32 * 512 + kmajor_addr(NA * wm + j));
+    else return *(const bf16x8*)(stage + xbase + j * 16 * kRowBytes + fragoff[ks]);
   };
   auto frag_w = [&](const char* stage, int ks, int i) {
-    if constexpr (TB) return read_kmajor(stage + ks * 16 * 512 + tfoW[i]);
-    else return *(const bf16x8*)(stage + wbase + i * 32 * kRowBytes + fragoff[ks]);
+    if constexpr (TB) return read_kmajor(stage + BM * kRowBytes + ks * 32 * 512 + kmajor_addr(NW * wn + i));
+    else return *(const bf16x8*)(stage + wbase + i * 16 * kRowBytes + fragoff[ks]);
   };
 
-  f32x16 acc[4][XF];
+  f32x4 acc[NW][NA];
 #pragma unroll
-  for (int i = 0; i < 4; ++i)
+  for (int i = 0; i < NW; ++i)
 #pragma unroll
-    for (int j = 0; j < XF; ++j)
+    for (int j = 0; j < NA; ++j)
 #pragma unroll
-      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+      for (int v = 0; v < 4; ++v) acc[i][j][v] = 0.f;
 
-  // ---- main loop: two LDS stages of 64 K-columns, and two register sets of fragments
-  // alternating over the four 16-wide slices so that the ds_reads of the next slice are in
-  // flight while the MFMAs of the current one run.  One barrier per step, placed after the
-  // reads of the step's last slice have been issued: past it nobody reads the current stage any
-  // more, so the loads of step kt+2 can start into it, and the next stage (whose loads every
-  // wave has waited for before the barrier) can be read.
+  // ---- main loop: two LDS stages of 64 K-columns.  One barrier per step, placed after the last
+  // reads of the stage have been issued: past it nobody reads the current stage any more, so the
+  // loads of step kt+2 can start into it, and the next stage (whose loads every wave has waited for
+  // before the barrier) can be read.
   //
   // The loads of step kt+2 are not issued in one burst: a wave that issues a burst stands still
-  // until the texture unit has accepted it, and the MFMA pipe with it.  Six (eight when an
-  // operand is k-major) go out during the slice after barrier kt, the rest during slice 0 of
-  // step kt+1, none in slices 1 and 2, which leaves every load two slices to land before the
-  // wait at the end of step kt+1; the activation loads go first.  (Measured on three workloads with k-contiguous operands: 6 + rest
-  // + 0 beats 8 + half + half by 2-11 %, and 4, 5, 7, 8, 10, 12 or all 16 after the barrier;
-  // activations first is 0.7 % ahead of weights first on the first GEMM and level on the second.
-  // With k-major weights 8 after the barrier is 0.5-2 % ahead of 6, 10 level, 4, 12 and 16 behind.)
+  // until the texture unit has accepted it, and the MFMA pipe with it.  kAfterBarrier of them go
+  // out during the unit after barrier kt, the rest during the first unit of step kt+1, none in
+  // the two units before the next barrier, which leaves every load two units to land before the
+  // wait at the end of step kt+1; the activation loads go first.
   const int k_steps = (K + BK - 1) / BK;
   constexpr int kLoads = kLoadsW + kLoadsX;
   auto issue = [&](int stage, int step, int q0, int q1) {
@@ -509,46 +504,58 @@ __device__ __forceinline__ void gemm_tile(const MfmaArgs& a, char* smem, int slo
       }
     }
   };
-  constexpr int kDsReads = (TB ? 8 : 4) + (TA ? 2 * XF : XF);  // LDS read instructions per slice
-  constexpr int kWanted = MODE == MODE_NT ? 6 : 8;
-  constexpr int kAfterBarrier = kWanted < kLoads ? kWanted : kLoads;  // loads issued in the slice after the barrier,
-  constexpr int kSlice0 = kLoads - kAfterBarrier;  // and in slice 0 of the next step
-  bf16x8 xf[2][XF], wf[2][4];
-  // read order = order of first use by the MFMAs (weight fragment 0, all activation fragments,
-  // weight fragments 1..3)
-  auto read_frags = [&](const char* stage, int ks, int set) {
-    wf[set][0] = frag_w(stage, ks, 0);
-#pragma unroll
-    for (int j = 0; j < XF; ++j) xf[set][j] = frag_x(stage, ks, j);
-#pragma unroll
-    for (int i = 1; i < 4; ++i) wf[set][i] = frag_w(stage, ks, i);
+  // A stage is consumed as four units: 32-wide slice s (0, 1) x half hw (0, 1) of the wave's weight
+  // fragments.  Unit (s, hw) needs the NA activation fragments of slice s and the weight fragments
+  // 4 hw .. 4 hw + 3 of slice s: 4 NA MFMAs.  Two register sets of each kind alternate (activation
+  // fragments by slice, weight fragments by unit), so that the ds_reads of the next unit are in
+  // flight while the MFMAs of the current one run.
+  //
+  // The MFMAs are written as assembly with the accumulator tied to the destination (left to the
+  // register allocator, this MFMA shape gets a destination different from its accumulator input,
+  // and with all 256 accumulator registers live the copies that needs go through VGPRs: 3.5 moves
+  // per MFMA).  A volatile asm also pins the order: memory operations do not cross it, so the
+  // fragment reads and direct-to-LDS loads below issue exactly where they are written, one read per
+  // MFMA from the start of a unit (the next unit waits on them), the loads spread over the unit.
+  constexpr int kMfmas = 4 * NA;                             // MFMAs per unit
+  // (Measured on configs 2 and 3: 12 after the barrier is 1-2 % ahead of 8 and 10, 3-5 % ahead of 6, 14 and 16;
+  // spreading a unit's loads over the whole unit beats its first half or quarter by 1-3 %; a barrier moved up
+  // to just behind the stage's last reads, with all loads after it, is level.)
+  constexpr int kWanted = 12;
+  constexpr int kAfterBarrier = kWanted < kLoads ? kWanted : kLoads;  // loads issued in the unit after the barrier,
+  bf16x8 xf[2][NA], wf[2][4];
+  // r-th fragment read of a unit's look-ahead: the weight fragments of unit (s, hw) go into set ws,
+  // the activation fragments [j0, j1) of slice xs into set xset; with x_first in the order of first
+  // use by the MFMAs (weight fragment 0, the activation fragments, weight fragments 1..3).
+  auto read_r = [&](int r, const char* w_stage, int s, int hw, int ws, const char* x_stage, int xs, int xset, int j0,
+                    int j1, bool x_first) {
+    const int NX = j1 - j0;
+    int wi = -1, xj = -1;
+    if (x_first) {
+      if (r == 0) wi = 0;
+      else if (r <= NX) xj = j0 + r - 1;
+      else wi = r - NX;
+    } else {
+      if (r < 4) wi = r;
+      else xj = j0 + r - 4;
+    }
+    if (wi >= 0) wf[ws][wi] = frag_w(w_stage, s, 4 * hw + wi);
+    else xf[xset][xj] = frag_x(x_stage, xs, xj);
   };
-  auto read_one = [&](const char* stage, int ks, int set, int r) {  // r-th fragment in that order
-    if (r == 0) wf[set][0] = frag_w(stage, ks, 0);
-    else if (r <= XF) xf[set][r - 1] = frag_x(stage, ks, r - 1);
-    else wf[set][r - XF] = frag_w(stage, ks, r - XF);
-  };
-  // Fragment reads and direct-to-LDS loads of one slice, alternating in program order.  The
-  // compiler cannot tell that a load's LDS destination and a fragment read never overlap, so it
-  // keeps the two kinds in the order written: written as "all loads, then all reads", the reads
-  // would reach the LDS queue only after the last load and the next slice's first MFMAs would
-  // each wait out an LDS round trip.
-  auto reads_and_loads = [&](const char* rd_stage, int ks, int set, int ld_stage, int step, int q0, int q1) {
-    constexpr int NR = 4 + XF;
-    const int NL = q1 - q0;
+  // One unit: the MFMAs of weight half hw on the sets (xset, ws), interleaved with the reads for the
+  // next unit and the loads [q0, q1) of (ld_stage, step).
+  auto unit = [&](int hw, int xset, int ws, const char* w_stage, int ns, int nhw, int nws, const char* x_stage, int xs,
+                  int nxset, int j0, int j1, bool x_first, int ld_stage, int step, int q0, int q1) {
+    const int NR = 4 + (j1 - j0), NL = q1 - q0;
 #pragma unroll
-    for (int r = 0; r < NR; ++r) {
-      read_one(rd_stage, ks, set, r);
-      issue(ld_stage, step, q0 + (NL * r) / NR, q0 + (NL * (r + 1)) / NR);
+    for (int m = 0; m < kMfmas; ++m) {
+      if (m < NR) read_r(m, w_stage, ns, nhw, nws, x_stage, xs, nxset, j0, j1, x_first);
+      issue(ld_stage, step, q0 + (NL * m) / kMfmas, q0 + (NL * (m + 1)) / kMfmas);
+      asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0"
+                   : "+a"(acc[4 * hw + m / NA][m % NA])
+                   : "v"(wf[ws][m / NA]), "v"(xf[xset][m % NA]));
     }
   };
-  auto mma = [&](int set) {
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-      for (int j = 0; j < XF; ++j)
-        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[set][i], xf[set][j], acc[i][j], 0, 0, 0);
-  };
+  constexpr int kHalf = NA / 2;
 
   if constexpr (GATHER) {
     issue(0, 0, kLoadsX, kLoads);                        // the weight tile of step 0 does not need the row map
@@ -569,29 +576,29 @@ __device__ __forceinline__ void gemm_tile(const MfmaArgs& a, char* smem, int slo
   }
   issue(1, 1, 0, kAfterBarrier);
   // s_waitcnt with only vmcnt set (bits [3:0] and [15:14]): stage 1's first loads may still be in flight
-  __builtin_amdgcn_s_waitcnt(0x0F70 | kAfterBarrier);
+  __builtin_amdgcn_s_waitcnt(0x0F70 | (kAfterBarrier & 15) | ((kAfterBarrier >> 4) << 14));
   __syncthreads();
-  read_frags(smem, 0, 0);
+#pragma unroll
+  for (int r = 0; r < 4 + NA; ++r) read_r(r, smem, 0, 0, 0, smem, 0, 0, 0, NA, true);  // unit (0, 0) of stage 0
 
   for (int kt = 0; kt < k_steps; ++kt) {
     const int cur = kt & 1;
     const char* st = smem + cur * kStageBytes;
     const char* nx = smem + (cur ^ 1) * kStageBytes;
-    reads_and_loads(st, 1, 1, cur ^ 1, kt + 1, kAfterBarrier, kLoads);
-    mma(0);
-    sched_slice<0, kDsReads, 4 * XF, kSlice0>();
-    read_frags(st, 2, 0);
-    mma(1);
-    sched_slice<0, kDsReads, 4 * XF, 0>();
-    read_frags(st, 3, 1);
-    mma(0);
-    sched_slice<0, kDsReads, 4 * XF, 0>();
+    // unit (0, 0) runs; weight fragments of (0, 1), first half of slice 1's activation fragments
+    unit(0, 0, 0, st, 0, 1, 1, st, 1, 1, 0, kHalf, false, cur ^ 1, kt + 1, kAfterBarrier, kLoads);
+    // unit (0, 1) runs; weight fragments of (1, 0), the rest of slice 1's activation fragments
+    unit(1, 0, 1, st, 1, 0, 0, st, 1, 1, kHalf, NA, false, 0, 0, 0, 0);
+    // unit (1, 0) runs; weight fragments of (1, 1): the last reads of this stage
+    unit(0, 1, 0, st, 1, 1, 1, st, 1, 1, 0, 0, false, 0, 0, 0, 0);
     __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wave's loads of the next stage are in LDS
     __syncthreads();                     // everyone's are; nobody reads stage `cur` any more
-    reads_and_loads(nx, 0, 0, cur, kt + 2, 0, kAfterBarrier);
-    mma(1);
-    sched_slice<0, kDsReads, 4 * XF, kAfterBarrier>();
+    // unit (1, 1) runs; all of unit (0, 0) of the next stage
+    unit(1, 1, 1, nx, 0, 0, 0, nx, 0, 0, 0, NA, true, cur, kt + 2, 0, kAfterBarrier);
   }
+  // the compiler does not know that the assembly above is MFMAs: keep their results away from the
+  // VALU reads of the epilogue for the wait states such reads need (at most 18)
+  asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
   // The trailing loads (steps past the end of K, zero-length descriptor) still write zeros into
   // stage `cur`, and each wave only waits for its own: with an odd number of K steps that is
   // stage 0, where the epilogue patches of the other waves lie.  Drain this wave's, then wait
@@ -599,33 +606,34 @@ __device__ __forceinline__ void gemm_tile(const MfmaArgs& a, char* smem, int slo
   __builtin_amdgcn_s_waitcnt(0x0F70);
   __syncthreads();
 
-  // ---- epilogue.  acc[i][j] is the 32x32 block (weight fragment i) x (activation fragment j);
-  // lane l holds activation row j*32 + l%32 and, for g = 0..3, the 4 consecutive weight rows
-  // i*32 + 8g + 4*(l/32) + 0..3  -> 4 consecutive output columns.  Stored straight from there,
-  // a wave store would touch 32 rows with 16 bytes each; such partial-line writes cost the
-  // second GEMM 10 % (timed with the stores removed).  So each 32-row fragment goes through a
-  // per-wave LDS patch (the stages are dead by now; LDS serves a wave's accesses in order) and
-  // leaves as 16 bytes per lane, whole 128-byte lines at a time.
+  // ---- epilogue.  acc[i][j] is the 16x16 block (weight fragment i) x (activation fragment j);
+  // lane l holds activation row j*16 + l%16 and the 4 consecutive weight rows i*16 + 4*(l/16) + 0..3
+  // -> 4 consecutive output columns.  Stored straight from there, a wave store would touch 16
+  // rows with 8 bytes each; such partial-line writes cost the second GEMM 10 % (timed with the
+  // stores removed).  So 32 rows at a time go through a per-wave LDS patch (the stages are dead by
+  // now; LDS serves a wave's accesses in order) and leave as 16 bytes per lane, whole 128-byte
+  // lines at a time.
   constexpr int kWaveCols = kGated ? 64 : 128;             // output columns of this wave
   constexpr int kPitch = kWaveCols * 2 + 16;               // patch row in bytes: 16-byte aligned, rows 4 banks apart
   constexpr int kLanesPerRow = kWaveCols / 8;              // 16-byte pieces of a patch row
   constexpr int kRowsPerStore = 64 / kLanesPerRow;
   char* const patch = smem + wave * (32 * kPitch);
-  const int half = lane >> 5;
-  // One pass of fragment j through the patch: value(blk, v) is the number for patch column
-  // blk*32 + 8*(v/4) + 4*half + v%4; the patch then leaves for dst[row, col0 + ...], columns
-  // from col_end on are not stored.
-  auto pass = [&](int j, auto value, uint16_t* dst, int ld, int col0, int col_end) {
-    char* const prow = patch + (lane & 31) * kPitch;
+  const int quad = lane >> 4;
+  // One pass of the 32 activation rows [32 jj, 32 jj + 32) through the patch: value(c, h, v) is the
+  // number for patch row 16 h + l%16, patch column 16 c + 4 quad + v; the patch then leaves for
+  // dst[row, col0 + ...], columns from col_end on are not stored.
+  auto pass = [&](int jj, auto value, uint16_t* dst, int ld, int col0, int col_end) {
 #pragma unroll
-    for (int blk = 0; blk < kWaveCols / 32; ++blk)
+    for (int h = 0; h < 2; ++h) {
+      char* const prow = patch + (16 * h + (lane & 15)) * kPitch;
 #pragma unroll
-      for (int g = 0; g < 4; ++g) {
+      for (int c = 0; c < kWaveCols / 16; ++c) {
         uint2 pk;
-        pk.x = pack_bf16x2(value(blk, 4 * g), value(blk, 4 * g + 1));
-        pk.y = pack_bf16x2(value(blk, 4 * g + 2), value(blk, 4 * g + 3));
-        *(uint2*)(prow + (blk * 32 + 8 * g + 4 * half) * 2) = pk;
+        pk.x = pack_bf16x2(value(c, h, 0), value(c, h, 1));
+        pk.y = pack_bf16x2(value(c, h, 2), value(c, h, 3));
+        *(uint2*)(prow + (c * 16 + 4 * quad) * 2) = pk;
       }
+    }
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");  // keep the patch writes before the reads below
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
@@ -633,7 +641,7 @@ __device__ __forceinline__ void gemm_tile(const MfmaArgs& a, char* smem, int slo
     for (int t = 0; t < 32 / kRowsPerStore; ++t) {
       const int r = t * kRowsPerStore + lane / kLanesPerRow, piece = lane % kLanesPerRow;
       const uint4 v = *(const uint4*)(patch + r * kPitch + piece * 16);
-      const int row = row0 + wm * 32 * XF + j * 32 + r;
+      const int row = row0 + wm * 32 * XF + jj * 32 + r;
       const int col = col0 + piece * 8;  // row lengths are multiples of 8
       if (row < row_end && col < col_end) *(uint4*)(dst + (size_t)row * ld + col) = v;
     }
@@ -649,14 +657,18 @@ __device__ __forceinline__ void gemm_tile(const MfmaArgs& a, char* smem, int slo
     constexpr int kPitchF = 32 * 4 + 16;
     char* const patchf = smem + wave * (32 * kPitchF);
 #pragma unroll
-    for (int j = 0; j < XF; ++j)
+    for (int jj = 0; jj < XF; ++jj)
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        char* const prow = patchf + (lane & 31) * kPitchF;
+      for (int ii = 0; ii < 4; ++ii) {
 #pragma unroll
-        for (int g = 0; g < 4; ++g) {
-          const float4 v = {acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]};
-          *(float4*)(prow + (8 * g + 4 * half) * 4) = v;
+        for (int h = 0; h < 2; ++h) {
+          char* const prow = patchf + (16 * h + (lane & 15)) * kPitchF;
+#pragma unroll
+          for (int c = 0; c < 2; ++c) {
+            const f32x4& blk = acc[2 * ii + c][2 * jj + h];
+            const float4 v = {blk[0], blk[1], blk[2], blk[3]};
+            *(float4*)(prow + (16 * c + 4 * quad) * 4) = v;
+          }
         }
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
@@ -665,8 +677,8 @@ __device__ __forceinline__ void gemm_tile(const MfmaArgs& a, char* smem, int slo
         for (int t = 0; t < 4; ++t) {
           const int r = t * 8 + (lane >> 3), piece = lane & 7;
           const float4 v = *(const float4*)(patchf + r * kPitchF + piece * 16);
-          const int row = row0 + wm * 32 * XF + j * 32 + r;
-          const int col = n0 + wn * 128 + i * 32 + piece * 4;  // row lengths are multiples of 8
+          const int row = row0 + wm * 32 * XF + jj * 32 + r;
+          const int col = n0 + wn * 128 + ii * 32 + piece * 4;  // row lengths are multiples of 8
           if (row < row_end && col < a.n_out) {
             float4* const dst = (float4*)(a.Cacc + (size_t)row * a.n_out + col);
             float4 c = *dst;
@@ -683,24 +695,30 @@ __device__ __forceinline__ void gemm_tile(const MfmaArgs& a, char* smem, int slo
       }
     return;
   }
+  // Gated weights: the tile's 32-column groups alternate gate and up columns, so of a wave's eight
+  // 16-wide weight fragments 0, 1, 4, 5 are gate columns and i + 2 holds the up columns of the same
+  // outputs; output column block c (16 wide) of the wave comes from fragment 4 (c/2) + c%2.
+  auto gate_frag = [](int c) { return 4 * (c >> 1) + (c & 1); };
 #pragma unroll
-  for (int j = 0; j < XF; ++j) {
+  for (int jj = 0; jj < XF; ++jj) {
     if constexpr (EPI == EPI_SWIGLU) {
-      pass(j, [&](int q, int v) { return silu_fast(acc[2 * q][j][v]) * acc[2 * q + 1][j][v]; }, a.C, a.n_out, out0,
-           a.n_out);
+      pass(jj, [&](int c, int h, int v) { return silu_fast(acc[gate_frag(c)][2 * jj + h][v]) * acc[gate_frag(c) + 2][2 * jj + h][v]; },
+           a.C, a.n_out, out0, a.n_out);
     } else if constexpr (EPI == EPI_SWIGLU_KEEP) {
-      pass(j, [&](int q, int v) { return acc[2 * q][j][v]; }, a.Z, a.z_cols, out0, a.n_out);
-      pass(j, [&](int q, int v) { return acc[2 * q + 1][j][v]; }, a.Z, a.z_cols, a.up_row0 + out0,
+      pass(jj, [&](int c, int h, int v) { return acc[gate_frag(c)][2 * jj + h][v]; }, a.Z, a.z_cols, out0, a.n_out);
+      pass(jj, [&](int c, int h, int v) { return acc[gate_frag(c) + 2][2 * jj + h][v]; }, a.Z, a.z_cols, a.up_row0 + out0,
            a.up_row0 + a.n_out);
-      pass(j, [&](int q, int v) { return silu_fast(rounded(acc[2 * q][j][v])) * rounded(acc[2 * q + 1][j][v]); },
+      pass(jj, [&](int c, int h, int v) {
+             return silu_fast(rounded(acc[gate_frag(c)][2 * jj + h][v])) * rounded(acc[gate_frag(c) + 2][2 * jj + h][v]);
+           },
            a.C, a.n_out, out0, a.n_out);
     } else if constexpr (EPI == EPI_GELU_KEEP) {
-      pass(j, [&](int i, int v) { return acc[i][j][v]; }, a.Z, a.z_cols, out0, a.n_out);
-      pass(j, [&](int i, int v) { return gelu_fast(rounded(acc[i][j][v])); }, a.C, a.n_out, out0, a.n_out);
+      pass(jj, [&](int c, int h, int v) { return acc[c][2 * jj + h][v]; }, a.Z, a.z_cols, out0, a.n_out);
+      pass(jj, [&](int c, int h, int v) { return gelu_fast(rounded(acc[c][2 * jj + h][v])); }, a.C, a.n_out, out0, a.n_out);
     } else if constexpr (EPI == EPI_GELU) {
-      pass(j, [&](int i, int v) { return gelu_fast(acc[i][j][v]); }, a.C, a.n_out, out0, a.n_out);
+      pass(jj, [&](int c, int h, int v) { return gelu_fast(acc[c][2 * jj + h][v]); }, a.C, a.n_out, out0, a.n_out);
     } else {
-      pass(j, [&](int i, int v) { return acc[i][j][v]; }, a.C, a.n_out, out0, a.n_out);
+      pass(jj, [&](int c, int h, int v) { return acc[c][2 * jj + h][v]; }, a.C, a.n_out, out0, a.n_out);
     }
   }
 }
