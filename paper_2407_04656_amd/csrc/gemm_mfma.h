@@ -23,6 +23,7 @@
 #pragma once
 #include "lz_common.h"
 #include <atomic>
+#include <type_traits>
 
 namespace {
 
@@ -230,6 +231,16 @@ __device__ __forceinline__ void load16_to_lds(i32x4 rsrc, uint32_t lds_base, int
                :
                : "s"(lds_base), "v"(voffset), "s"(rsrc), "s"(soffset)
                : "memory");  // m0 is scratch to the compiler as well: it loads it right before each use
+}
+
+// The same load with an MFMA between the write of M0 and the load: the MFMA stands in for the wait
+// state the hardware wants there, and the three instructions fit the gap between two MFMAs.
+__device__ __forceinline__ void mfma_then_load16_to_lds(f32x4& acc, const bf16x8& w, const bf16x8& x, i32x4 rsrc,
+                                                        uint32_t lds_base, int voffset, int soffset) {
+  asm volatile("s_mov_b32 m0, %3\n\tv_mfma_f32_16x16x32_bf16 %0, %1, %2, %0\n\tbuffer_load_dwordx4 %4, %5, %6 offen lds"
+               : "+a"(acc)
+               : "v"(w), "v"(x), "s"(lds_base), "v"(voffset), "s"(rsrc), "s"(soffset)
+               : "memory");
 }
 
 // Activations on the fp32 accumulators of the bf16 path.  The result is rounded to bf16
@@ -469,7 +480,9 @@ __device__ __forceinline__ void gemm_tile(const MfmaArgs& a, char* smem, int slo
   // wait at the end of step kt+1; the activation loads go first.
   const int k_steps = (K + BK - 1) / BK;
   constexpr int kLoads = kLoadsW + kLoadsX;
-  auto issue = [&](int stage, int step, int q0, int q1) {
+  // with_mfma: an MFMA (accumulator, weight and activation fragment) to issue together with load q0
+  auto issue = [&](int stage, int step, int q0, int q1, f32x4* with_mfma = nullptr, const bf16x8* mw = nullptr,
+                   const bf16x8* mx = nullptr) {
     // a step past the end of K is "loaded" through a zero-length descriptor: no memory traffic
     const bool real = step < k_steps;
     const __amdgpu_buffer_rsrc_t ra = real ? rsrcA : rsrcNull;
@@ -489,8 +502,13 @@ __device__ __forceinline__ void gemm_tile(const MfmaArgs& a, char* smem, int slo
       const uint32_t ldsX = lds0 + stage * kStageBytes, ldsW = ldsX + BM * kRowBytes;
 #pragma unroll
       for (int q = q0; q < q1; ++q) {
-        if (q < kLoadsX) load16_to_lds(wa, ldsX + (wave * kLoadsX + q) * 1024, voffX[q], step * stepA);
-        else load16_to_lds(wb, ldsW + (wave * kLoadsW + q - kLoadsX) * 1024, voffW[q - kLoadsX], step * stepW);
+        const bool isx = q < kLoadsX;
+        const i32x4 words = isx ? wa : wb;
+        const uint32_t lds = isx ? ldsX + (wave * kLoadsX + q) * 1024 : ldsW + (wave * kLoadsW + q - kLoadsX) * 1024;
+        const int voff = isx ? voffX[q < kLoadsX ? q : 0] : voffW[q >= kLoadsX ? q - kLoadsX : 0];
+        const int soff = isx ? step * stepA : step * stepW;
+        if (with_mfma != nullptr && q == q0) mfma_then_load16_to_lds(*with_mfma, *mw, *mx, words, lds, voff, soff);
+        else load16_to_lds(words, lds, voff, soff);
       }
       return;
     }
@@ -552,10 +570,15 @@ __device__ __forceinline__ void gemm_tile(const MfmaArgs& a, char* smem, int slo
 #pragma unroll
     for (int m = 0; m < kMfmas; ++m) {
       if (m < NR) read_r(m, w_stage, ns, nhw, nws, x_stage, xs, nxset, j0, j1, x_first);
-      issue(ld_stage, step, q0 + (NL * m) / kMfmas, q0 + (NL * (m + 1)) / kMfmas);
-      asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0"
-                   : "+a"(acc[4 * hw + m / NA][m % NA])
-                   : "v"(wf[ws][m / NA]), "v"(xf[xset][m % NA]));
+      const int l0 = q0 + (NL * m) / kMfmas, l1 = q0 + (NL * (m + 1)) / kMfmas;
+      if (MODE != MODE_NT && l1 > l0) {
+        issue(ld_stage, step, l0, l1, &acc[4 * hw + m / NA][m % NA], &wf[ws][m / NA], &xf[xset][m % NA]);
+      } else {
+        issue(ld_stage, step, l0, l1);
+        asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0"
+                     : "+a"(acc[4 * hw + m / NA][m % NA])
+                     : "v"(wf[ws][m / NA]), "v"(xf[xset][m % NA]));
+      }
     }
   };
   constexpr int kHalf = NA / 2;
@@ -584,8 +607,12 @@ __device__ __forceinline__ void gemm_tile(const MfmaArgs& a, char* smem, int slo
 #pragma unroll
   for (int r = 0; r < 4 + NA; ++r) read_r(r, smem, 0, 0, 0, smem, 0, 0, 0, NA, true);  // unit (0, 0) of stage 0
 
-  for (int kt = 0; kt < k_steps; ++kt) {
-    const int cur = kt & 1;
+  // One K step on stage `cur`.  The loop below runs two steps per iteration, so that the stage is a
+  // compile-time constant and every LDS address of the step folds into an instruction's offset
+  // field or a literal (otherwise a dozen address additions per step queue up at the head of the
+  // loop and in front of the loads, and the MFMA pipe waits for them).
+  auto k_step = [&](int kt, auto cur_c) {
+    constexpr int cur = decltype(cur_c)::value;
     const char* st = smem + cur * kStageBytes;
     const char* nx = smem + (cur ^ 1) * kStageBytes;
     // unit (0, 0) runs; weight fragments of (0, 1), first half of slice 1's activation fragments
@@ -598,6 +625,14 @@ __device__ __forceinline__ void gemm_tile(const MfmaArgs& a, char* smem, int slo
     __syncthreads();                     // everyone's are; nobody reads stage `cur` any more
     // unit (1, 1) runs; all of unit (0, 0) of the next stage
     unit(1, 1, 1, nx, 0, 0, 0, nx, 0, 0, 0, NA, true, cur, kt + 2, 0, kAfterBarrier);
+  };
+  {
+    int kt = 0;
+    for (; kt + 1 < k_steps; kt += 2) {
+      k_step(kt, std::integral_constant<int, 0>{});
+      k_step(kt + 1, std::integral_constant<int, 1>{});
+    }
+    if (kt < k_steps) k_step(kt, std::integral_constant<int, 0>{});
   }
   // the compiler does not know that the assembly above is MFMAs: keep their results away from the
   // VALU reads of the epilogue for the wait states such reads need (at most 18)
