@@ -30,9 +30,9 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 # HBM-side bytes per launch of the dominant kernel, from the rocprofv3 FETCH_SIZE / WRITE_SIZE passes
 # summarised in profiles/<workload>_hbm_traffic.md (counters cannot be read from inside this
 # process, so the figure is carried here and re-measured whenever the kernel changes).
-# c2_mixtral GEMM-1: FETCH_SIZE 6 823 224 KiB x 2.00 (what the counter reads for a plain copy of known
-# size) + WRITE_SIZE 459 402 KiB.
-MEASURED_TRAFFIC_BYTES = {"c2_mixtral": 14.44e9}
+# c2_mixtral GEMM-1: FETCH_SIZE x 2.00 (what the counter reads for a plain copy of known size) +
+# WRITE_SIZE 459 402 KiB, from profiles/c2_mixtral_hbm_traffic.md.
+MEASURED_TRAFFIC_BYTES = {"c2_mixtral": 14.63e9}
 
 NAMES = ["route", "plan", "permute", "ffn_up", "ffn_down", "combine"]
 
