@@ -542,7 +542,8 @@ __device__ __forceinline__ void gemm_tile(const MfmaArgs& a, char* smem, int slo
   // spreading a unit's loads over the whole unit beats its first half or quarter by 1-3 %; a barrier moved up
   // to just behind the stage's last reads, with all loads after it, is level.)
   constexpr int kWanted = 12;
-  constexpr int kAfterBarrier = kWanted < kLoads ? kWanted : kLoads;  // loads issued in the unit after the barrier,
+  // loads issued in the unit after the barrier; the rest go with the first unit of the next step
+  constexpr int kAfterBarrier = kWanted < kLoads ? kWanted : kLoads;
   bf16x8 xf[2][NA], wf[2][4];
   // r-th fragment read of a unit's look-ahead: the weight fragments of unit (s, hw) go into set ws,
   // the activation fragments [j0, j1) of slice xs into set xset; with x_first in the order of first
