@@ -9,8 +9,8 @@
 // sustains 15 % more flops than one of v_mfma_f32_32x32x16_bf16 (2.03 against 1.76 PFLOP/s on
 // random operands; at a quarter of the CUs both reach the nominal rate).  Operand tiles are
 // streamed HBM -> LDS with 16-byte buffer loads that write LDS
-// directly, through two LDS stages of 64 k; fragment reads are software pipelined over two
-// register sets.  An operand may be k-contiguous ([row, k]: 256 tile rows of 128 B, read with
+// directly, through LDS stages of 64 k (two for the activation tile, three for the weight tile:
+// all 160 KiB); fragment reads are software pipelined over two register sets.  An operand may be k-contiguous ([row, k]: 256 tile rows of 128 B, read with
 // ds_read_b128) or k-major ([k, column]: 64 k-rows of 512 B, read with the transposing
 // ds_read_b64_tr_b16); see the MODE_* list below.  The XOR swizzles that keep the fragment
 // reads free of bank conflicts are applied on the global-address side, because a direct-to-LDS
@@ -170,8 +170,13 @@ __global__ __launch_bounds__(256) void build_tiles_kernel(const int32_t* __restr
 // ------------------------------------------------------------------------------------------
 constexpr int BM = 256, BN = 256, BK = 64;
 constexpr int kRowBytes = BK * 2;                  // one tile row of a stage in LDS: 128 B = 8 chunks of 16 B
-constexpr int kStageBytes = (BM + BN) * kRowBytes; // activation tile (up to 256 rows), then weight tile
-constexpr int kLdsBytes = 2 * kStageBytes;         // two stages: 128 KiB of the CU's 160 KiB
+constexpr int kATile = BM * kRowBytes, kWTile = BN * kRowBytes;  // 32 KiB each
+// LDS map: two activation stages, then a ring of three weight stages (its loads get two K steps
+// to land); together all of the CU's 160 KiB
+constexpr int kWStages = 3;
+constexpr int kLdsBytes = 2 * kATile + kWStages * kWTile;
+__device__ __forceinline__ constexpr int a_stage_off(int s) { return s * kATile; }
+__device__ __forceinline__ constexpr int w_stage_off(int w) { return 2 * kATile + w * kWTile; }
 
 struct MfmaArgs {
   const uint16_t* A;    // MODE_NT, MODE_NN: [P, K];  MODE_TN: [k_rows, lda]
@@ -431,7 +436,7 @@ __device__ __forceinline__ void gemm_tile(const MfmaArgs& a, char* smem, int slo
     for (int ks = 0; ks < KS; ++ks) fragoff[ks] = r * kRowBytes + (((ks * 4 + (lane >> 4)) ^ swz(r)) << 4);
   }
   const int xbase = wm * 32 * XF * kRowBytes;               // this wave's activation rows
-  const int wbase = BM * kRowBytes + wn * 128 * kRowBytes;  // this wave's 128 weight rows
+  const int wbase = wn * 128 * kRowBytes;                   // this wave's 128 weight rows
   // k-major tiles: lane 16g + q supplies the address of k-row 8g + q/4 of the 32-wide slice, column
   // quad q%4 of the fragment's 16 columns; the transposing read hands lane 16g + i column i at those
   // four k-rows, a second read 4 k-rows on completes the lane's 8 consecutive k.
@@ -451,13 +456,15 @@ __device__ __forceinline__ void gemm_tile(const MfmaArgs& a, char* smem, int slo
     const i16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) i16x4*)(p + 4 * 512));
     return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
   };
-  auto frag_x = [&](const char* stage, int ks, int j) {
-    if constexpr (TA) return read_kmajor(stage + ks * 32 * 512 + kmajor_addr(NA * wm + j));
-    else return *(const bf16x8*)(stage + xbase + j * 16 * kRowBytes + fragoff[ks]);
+  auto frag_x = [&](int stage, int ks, int j) {
+    const char* base = smem + a_stage_off(stage);
+    if constexpr (TA) return read_kmajor(base + ks * 32 * 512 + kmajor_addr(NA * wm + j));
+    else return *(const bf16x8*)(base + xbase + j * 16 * kRowBytes + fragoff[ks]);
   };
-  auto frag_w = [&](const char* stage, int ks, int i) {
-    if constexpr (TB) return read_kmajor(stage + BM * kRowBytes + ks * 32 * 512 + kmajor_addr(NW * wn + i));
-    else return *(const bf16x8*)(stage + wbase + i * 16 * kRowBytes + fragoff[ks]);
+  auto frag_w = [&](int stage, int ks, int i) {
+    const char* base = smem + w_stage_off(stage);
+    if constexpr (TB) return read_kmajor(base + ks * 32 * 512 + kmajor_addr(NW * wn + i));
+    else return *(const bf16x8*)(base + wbase + i * 16 * kRowBytes + fragoff[ks]);
   };
 
   f32x4 acc[NW][NA];
@@ -468,60 +475,62 @@ __device__ __forceinline__ void gemm_tile(const MfmaArgs& a, char* smem, int slo
 #pragma unroll
       for (int v = 0; v < 4; ++v) acc[i][j][v] = 0.f;
 
-  // ---- main loop: two LDS stages of 64 K-columns.  One barrier per step, placed after the last
-  // reads of the stage have been issued: past it nobody reads the current stage any more, so the
-  // loads of step kt+2 can start into it, and the next stage (whose loads every wave has waited for
+  // ---- main loop: K steps of 64 columns; step kt reads activation stage kt%2 and weight stage kt%3.
+  // One barrier per step, placed after the last reads of the step's stages have been issued: past it
+  // nobody reads them any more, so the activation loads of step kt+2 and the weight loads of step
+  // kt+3 can start into them, and the next step's stages (whose loads every wave has waited for
   // before the barrier) can be read.
   //
-  // The loads of step kt+2 are not issued in one burst: a wave that issues a burst stands still
-  // until the texture unit has accepted it, and the MFMA pipe with it.  kAfterBarrier of them go
-  // out during the unit after barrier kt, the rest during the first unit of step kt+1, none in
-  // the two units before the next barrier, which leaves every load two units to land before the
-  // wait at the end of step kt+1; the activation loads go first.
+  // A step's loads are not issued in one burst: a wave that issues a burst stands still until the
+  // texture unit has accepted it, and the MFMA pipe with it.  The activation loads go out during
+  // the unit after barrier kt (they must have landed by the next barrier); the weight loads, which
+  // have a whole step longer, are spread over the three units that follow.
   const int k_steps = (K + BK - 1) / BK;
   constexpr int kLoads = kLoadsW + kLoadsX;
+  // Loads [q0, q1) of a wave's 16 per step: the activation loads (q < kLoadsX) of K step a_step into
+  // activation stage a_stage, the weight loads of K step w_step into weight stage w_stage.
   // with_mfma: an MFMA (accumulator, weight and activation fragment) to issue together with load q0
-  auto issue = [&](int stage, int step, int q0, int q1, f32x4* with_mfma = nullptr, const bf16x8* mw = nullptr,
-                   const bf16x8* mx = nullptr) {
+  auto issue = [&](int a_stage, int a_step, int w_stage, int w_step, int q0, int q1, f32x4* with_mfma = nullptr,
+                   const bf16x8* mw = nullptr, const bf16x8* mx = nullptr) {
     // a step past the end of K is "loaded" through a zero-length descriptor: no memory traffic
-    const bool real = step < k_steps;
-    const __amdgpu_buffer_rsrc_t ra = real ? rsrcA : rsrcNull;
-    const __amdgpu_buffer_rsrc_t rb = real ? rsrcB : rsrcNull;
-    char* sX = smem + stage * kStageBytes;
-    char* sW = sX + BM * kRowBytes;
+    const bool real_a = a_step < k_steps, real_w = w_step < k_steps;
+    char* sX = smem + a_stage_off(a_stage);
+    char* sW = smem + w_stage_off(w_stage);
     if constexpr (MODE != MODE_NT) {
-      i32x4 wa = real ? wordsA : wordsNull, wb = real ? wordsB : wordsNull;
+      i32x4 wa = real_a ? wordsA : wordsNull, wb = real_w ? wordsB : wordsNull;
       if constexpr (MODE == MODE_TN) {
-        const unsigned long long offA = (unsigned long long)(unsigned)step * stepA64;
-        const unsigned long long offW = (unsigned long long)(unsigned)step * stepW64;
+        const unsigned long long offA = (unsigned long long)(unsigned)a_step * stepA64;
+        const unsigned long long offW = (unsigned long long)(unsigned)w_step * stepW64;
         const unsigned long long leftA = a_bytes > offA ? a_bytes - offA : 0ull;
         const unsigned long long leftW = w_bytes > offW ? w_bytes - offW : 0ull;
         wa = rsrc_words((const char*)tileA + offA, leftA > 0xFFFFFFFFull ? 0xFFFFFFFFu : (uint32_t)leftA);
         wb = rsrc_words((const char*)tileW + offW, leftW > 0xFFFFFFFFull ? 0xFFFFFFFFu : (uint32_t)leftW);
       }
-      const uint32_t ldsX = lds0 + stage * kStageBytes, ldsW = ldsX + BM * kRowBytes;
+      const uint32_t ldsX = lds0 + a_stage_off(a_stage), ldsW = lds0 + w_stage_off(w_stage);
 #pragma unroll
       for (int q = q0; q < q1; ++q) {
         const bool isx = q < kLoadsX;
         const i32x4 words = isx ? wa : wb;
         const uint32_t lds = isx ? ldsX + (wave * kLoadsX + q) * 1024 : ldsW + (wave * kLoadsW + q - kLoadsX) * 1024;
         const int voff = isx ? voffX[q < kLoadsX ? q : 0] : voffW[q >= kLoadsX ? q - kLoadsX : 0];
-        const int soff = isx ? step * stepA : step * stepW;
+        const int soff = isx ? a_step * stepA : w_step * stepW;
         if (with_mfma != nullptr && q == q0) mfma_then_load16_to_lds(*with_mfma, *mw, *mx, words, lds, voff, soff);
         else load16_to_lds(words, lds, voff, soff);
       }
       return;
     }
+    const __amdgpu_buffer_rsrc_t ra = real_a ? rsrcA : rsrcNull;
+    const __amdgpu_buffer_rsrc_t rb = real_w ? rsrcB : rsrcNull;
 #pragma unroll
     for (int q = q0; q < q1; ++q) {
       if (q < kLoadsX) {
         const int u = wave * kLoadsX + q;
         __builtin_amdgcn_raw_ptr_buffer_load_lds(ra, (__attribute__((address_space(3))) void*)(sX + u * 1024), 16,
-                                                 voffX[q], step * stepA, 0, 0);
+                                                 voffX[q], a_step * stepA, 0, 0);
       } else {
         const int u = wave * kLoadsW + (q - kLoadsX);
         __builtin_amdgcn_raw_ptr_buffer_load_lds(rb, (__attribute__((address_space(3))) void*)(sW + u * 1024), 16,
-                                                 voffW[q - kLoadsX], step * stepW, 0, 0);
+                                                 voffW[q - kLoadsX], w_step * stepW, 0, 0);
       }
     }
   };
@@ -538,17 +547,19 @@ __device__ __forceinline__ void gemm_tile(const MfmaArgs& a, char* smem, int slo
   // fragment reads and direct-to-LDS loads below issue exactly where they are written, one read per
   // MFMA from the start of a unit (the next unit waits on them), the loads spread over the unit.
   constexpr int kMfmas = 4 * NA;                             // MFMAs per unit
-  // (Measured on configs 2 and 3: 12 after the barrier is 1-2 % ahead of 8 and 10, 3-5 % ahead of 6, 14 and 16;
-  // spreading a unit's loads over the whole unit beats its first half or quarter by 1-3 %; a barrier moved up
+  // Loads [0, kAfterBarrier) go out in the unit after the barrier, [kAfterBarrier, kL1), [kL1, kL2) and
+  // [kL2, kLoads) in the three units of the next step: the 8 weight loads as 2 + 3 + 3.
+  // (Measured on configs 2-4: with the weight loads bunched behind the activation loads, 4 in the unit after
+  // the barrier and 4 in the next, the second GEMM is 3-5 % slower and the first level; all 16 after the barrier
+  // costs both 5-7 %; other even spreads, also with half of the activation loads a unit later, are within 1 %.
+  // Spreading a unit's loads over the whole unit beats its first half or quarter by 1-3 %; a barrier moved up
   // to just behind the stage's last reads, with all loads after it, is level.)
-  constexpr int kWanted = 12;
-  // loads issued in the unit after the barrier; the rest go with the first unit of the next step
-  constexpr int kAfterBarrier = kWanted < kLoads ? kWanted : kLoads;
+  constexpr int kAfterBarrier = kLoadsX, kL1 = kLoadsX + 2, kL2 = kLoadsX + 5;
   bf16x8 xf[2][NA], wf[2][4];
   // r-th fragment read of a unit's look-ahead: the weight fragments of unit (s, hw) go into set ws,
   // the activation fragments [j0, j1) of slice xs into set xset; with x_first in the order of first
   // use by the MFMAs (weight fragment 0, the activation fragments, weight fragments 1..3).
-  auto read_r = [&](int r, const char* w_stage, int s, int hw, int ws, const char* x_stage, int xs, int xset, int j0,
+  auto read_r = [&](int r, int w_stage, int s, int hw, int ws, int x_stage, int xs, int xset, int j0,
                     int j1, bool x_first) {
     const int NX = j1 - j0;
     int wi = -1, xj = -1;
@@ -564,18 +575,19 @@ __device__ __forceinline__ void gemm_tile(const MfmaArgs& a, char* smem, int slo
     else xf[xset][xj] = frag_x(x_stage, xs, xj);
   };
   // One unit: the MFMAs of weight half hw on the sets (xset, ws), interleaved with the reads for the
-  // next unit and the loads [q0, q1) of (ld_stage, step).
-  auto unit = [&](int hw, int xset, int ws, const char* w_stage, int ns, int nhw, int nws, const char* x_stage, int xs,
-                  int nxset, int j0, int j1, bool x_first, int ld_stage, int step, int q0, int q1) {
+  // next unit and the loads [q0, q1) of the activation and weight steps named by the ld_ arguments.
+  auto unit = [&](int hw, int xset, int ws, int w_stage, int ns, int nhw, int nws, int x_stage, int xs, int nxset, int j0,
+                  int j1, bool x_first, int ld_a_stage, int ld_a_step, int ld_w_stage, int ld_w_step, int q0, int q1) {
     const int NR = 4 + (j1 - j0), NL = q1 - q0;
 #pragma unroll
     for (int m = 0; m < kMfmas; ++m) {
       if (m < NR) read_r(m, w_stage, ns, nhw, nws, x_stage, xs, nxset, j0, j1, x_first);
       const int l0 = q0 + (NL * m) / kMfmas, l1 = q0 + (NL * (m + 1)) / kMfmas;
       if (MODE != MODE_NT && l1 > l0) {
-        issue(ld_stage, step, l0, l1, &acc[4 * hw + m / NA][m % NA], &wf[ws][m / NA], &xf[xset][m % NA]);
+        issue(ld_a_stage, ld_a_step, ld_w_stage, ld_w_step, l0, l1, &acc[4 * hw + m / NA][m % NA], &wf[ws][m / NA],
+              &xf[xset][m % NA]);
       } else {
-        issue(ld_stage, step, l0, l1);
+        issue(ld_a_stage, ld_a_step, ld_w_stage, ld_w_step, l0, l1);
         asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0"
                      : "+a"(acc[4 * hw + m / NA][m % NA])
                      : "v"(wf[ws][m / NA]), "v"(xf[xset][m % NA]));
@@ -584,8 +596,9 @@ __device__ __forceinline__ void gemm_tile(const MfmaArgs& a, char* smem, int slo
   };
   constexpr int kHalf = NA / 2;
 
+  constexpr int D = kWStages;
   if constexpr (GATHER) {
-    issue(0, 0, kLoadsX, kLoads);                        // the weight tile of step 0 does not need the row map
+    issue(0, 0, 0, 0, kLoadsX, kLoads);                  // the weight tile of step 0 does not need the row map
     __builtin_amdgcn_s_waitcnt(0x0F70 | kLoadsW);        // vmcnt: the index loads (issued before those) are back
     const uint32_t gk = (uint32_t)a.gather_k, n_pairs = (uint32_t)(a.gather_T * a.gather_k);
 #pragma unroll
@@ -597,50 +610,69 @@ __device__ __forceinline__ void gemm_tile(const MfmaArgs& a, char* smem, int slo
       // a row without a pair (never inside a slot) reads past the descriptor's end: zeros
       voffX[i] = pair < n_pairs ? (int)((pair / gk * (uint32_t)K + (uint32_t)chunk * 8u) * 2u) : (int)a_extent;
     }
-    issue(0, 0, 0, kLoadsX);
+    issue(0, 0, 0, 0, 0, kLoadsX);
   } else {
-    issue(0, 0, 0, kLoads);
+    issue(0, 0, 0, 0, 0, kLoads);
   }
-  issue(1, 1, 0, kAfterBarrier);
-  // s_waitcnt with only vmcnt set (bits [3:0] and [15:14]): stage 1's first loads may still be in flight
-  __builtin_amdgcn_s_waitcnt(0x0F70 | (kAfterBarrier & 15) | ((kAfterBarrier >> 4) << 14));
+  // in flight when the loop starts: the weights of step 1 and what the unit after a barrier issues
+  // (the activations of step 1); the units of step 0 issue the weight loads of step 2
+  constexpr int kAhead = kLoadsW + kAfterBarrier;
+  issue(1, 1, 1, 1, kLoadsX, kLoads);
+  issue(1, 1, 2, 2, 0, kAfterBarrier);
+  // s_waitcnt with only vmcnt set (bits [3:0] and [15:14]): the later steps' loads may still be in flight
+  __builtin_amdgcn_s_waitcnt(0x0F70 | (kAhead & 15) | ((kAhead >> 4) << 14));
   __syncthreads();
 #pragma unroll
-  for (int r = 0; r < 4 + NA; ++r) read_r(r, smem, 0, 0, 0, smem, 0, 0, 0, NA, true);  // unit (0, 0) of stage 0
+  for (int r = 0; r < 4 + NA; ++r) read_r(r, 0, 0, 0, 0, 0, 0, 0, 0, NA, true);  // unit (0, 0) of stage 0
 
-  // One K step on stage `cur`.  The loop below runs two steps per iteration, so that the stage is a
-  // compile-time constant and every LDS address of the step folds into an instruction's offset
-  // field or a literal (otherwise a dozen address additions per step queue up at the head of the
-  // loop and in front of the loads, and the MFMA pipe waits for them).
-  auto k_step = [&](int kt, auto cur_c) {
-    constexpr int cur = decltype(cur_c)::value;
-    const char* st = smem + cur * kStageBytes;
-    const char* nx = smem + (cur ^ 1) * kStageBytes;
+  // One K step on activation stage `as` and weight stage `wst`.  The loop below is unrolled so that
+  // both are compile-time constants and every LDS address of the step folds into an instruction's
+  // offset field or a literal (otherwise a dozen address additions per step queue up at the head of
+  // the loop and in front of the loads, and the MFMA pipe waits for them).
+  // Loads: after barrier kt the activations of step kt+2 go into the stage just read; the weights
+  // of step kt+3 follow in the units of step kt+1, into the weight stage freed by barrier kt.  A
+  // step's weight loads are thus still in flight at the next barrier, and its wait leaves the
+  // newest kLoadsW loads out.
+  auto k_step = [&](int kt, auto as_c, auto wst_c) {
+    constexpr int as = decltype(as_c)::value, wst = decltype(wst_c)::value;
+    constexpr int as_next = as ^ 1, wst_next = (wst + 1) % D, wst_prev = (wst + D - 1) % D;
     // unit (0, 0) runs; weight fragments of (0, 1), first half of slice 1's activation fragments
-    unit(0, 0, 0, st, 0, 1, 1, st, 1, 1, 0, kHalf, false, cur ^ 1, kt + 1, kAfterBarrier, kLoads);
+    unit(0, 0, 0, wst, 0, 1, 1, as, 1, 1, 0, kHalf, false, as_next, kt + 1, wst_prev, kt - 1 + D, kAfterBarrier, kL1);
     // unit (0, 1) runs; weight fragments of (1, 0), the rest of slice 1's activation fragments
-    unit(1, 0, 1, st, 1, 0, 0, st, 1, 1, kHalf, NA, false, 0, 0, 0, 0);
+    unit(1, 0, 1, wst, 1, 0, 0, as, 1, 1, kHalf, NA, false, as_next, kt + 1, wst_prev, kt - 1 + D, kL1, kL2);
     // unit (1, 0) runs; weight fragments of (1, 1): the last reads of this stage
-    unit(0, 1, 0, st, 1, 1, 1, st, 1, 1, 0, 0, false, 0, 0, 0, 0);
-    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wave's loads of the next stage are in LDS
-    __syncthreads();                     // everyone's are; nobody reads stage `cur` any more
-    // unit (1, 1) runs; all of unit (0, 0) of the next stage
-    unit(1, 1, 1, nx, 0, 0, 0, nx, 0, 0, 0, NA, true, cur, kt + 2, 0, kAfterBarrier);
+    unit(0, 1, 0, wst, 1, 1, 1, as, 1, 1, 0, 0, false, as_next, kt + 1, wst_prev, kt - 1 + D, kL2, kLoads);
+    // this wave's loads of the next step are in LDS ...
+    __builtin_amdgcn_s_waitcnt(0x0F70 | kLoadsW);
+    __syncthreads();  // ... everyone's are; nobody reads these stages any more
+    // unit (1, 1) runs; all of unit (0, 0) of the next step
+    unit(1, 1, 1, wst_next, 0, 0, 0, as_next, 0, 0, 0, NA, true, as, kt + 2, wst, kt + D, 0, kAfterBarrier);
   };
   {
+    using I0 = std::integral_constant<int, 0>;
+    using I1 = std::integral_constant<int, 1>;
+    using I2 = std::integral_constant<int, 2>;
     int kt = 0;
-    for (; kt + 1 < k_steps; kt += 2) {
-      k_step(kt, std::integral_constant<int, 0>{});
-      k_step(kt + 1, std::integral_constant<int, 1>{});
+    for (; kt + 5 < k_steps; kt += 6) {
+      k_step(kt, I0{}, I0{});
+      k_step(kt + 1, I1{}, I1{});
+      k_step(kt + 2, I0{}, I2{});
+      k_step(kt + 3, I1{}, I0{});
+      k_step(kt + 4, I0{}, I1{});
+      k_step(kt + 5, I1{}, I2{});
     }
-    if (kt < k_steps) k_step(kt, std::integral_constant<int, 0>{});
+    if (kt < k_steps) k_step(kt, I0{}, I0{});
+    if (kt + 1 < k_steps) k_step(kt + 1, I1{}, I1{});
+    if (kt + 2 < k_steps) k_step(kt + 2, I0{}, I2{});
+    if (kt + 3 < k_steps) k_step(kt + 3, I1{}, I0{});
+    if (kt + 4 < k_steps) k_step(kt + 4, I0{}, I1{});
   }
   // the compiler does not know that the assembly above is MFMAs: keep their results away from the
   // VALU reads of the epilogue for the wait states such reads need (at most 18)
   asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
   // The trailing loads (steps past the end of K, zero-length descriptor) still write zeros into
-  // stage `cur`, and each wave only waits for its own: with an odd number of K steps that is
-  // stage 0, where the epilogue patches of the other waves lie.  Drain this wave's, then wait
+  // their stages, and each wave only waits for its own: one of those stages is activation stage 0,
+  // where the epilogue patches of the other waves lie.  Drain this wave's, then wait
   // until every wave has drained its own, before anybody writes a patch.
   __builtin_amdgcn_s_waitcnt(0x0F70);
   __syncthreads();
