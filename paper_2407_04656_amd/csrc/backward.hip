@@ -320,6 +320,10 @@ int32_t gemm_wgrad(const uint16_t* A, const uint16_t* W, uint16_t* C, float* Cac
   g.slot_offsets = slot_offsets;
   g.k_rows = P;
   g.rows_per_slot = rows_per_slot;
+  // 32-bit byte offsets do if no operand reaches 4 GiB, the K steps past a slot's end included
+  const int ld_max = rows_per_slot > n_out ? rows_per_slot : n_out;
+  const bool wide = ((unsigned long long)P + 4 * BK) * (unsigned)ld_max * 2ull > 0xFFFFFFFFull;
+  if (wide) return Cacc ? launch_mfma<EPI_ACCUM, MODE_TN_WIDE>(g, st) : launch_mfma<EPI_NONE, MODE_TN_WIDE>(g, st);
   return Cacc ? launch_mfma<EPI_ACCUM, MODE_TN>(g, st) : launch_mfma<EPI_NONE, MODE_TN>(g, st);
 }
 

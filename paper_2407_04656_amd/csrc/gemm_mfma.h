@@ -210,14 +210,16 @@ struct MfmaArgs {
 // Operand layouts of the contraction C[m, n] = sum_k A(m, k) W(n, k):
 //   MODE_NT  A [m, k], W [n, k]: both contiguous along k (the data gradients)
 //   MODE_NN  A [m, k], W [k, n] (the forward: weights are stored input-major)
-//   MODE_TN  A [k, m], W [k, n], a different k range for every slot
+//   MODE_TN  A [k, m], W [k, n], a different k range for every slot (the weight gradients)
+//   MODE_TN_WIDE  the same when an operand may span more than 4 GiB inside one slot (64-bit
+//            arithmetic where MODE_TN rebuilds its buffer descriptors for a K step)
 // A k-major operand tile lies in LDS as 64 k-rows of 256 columns (512 B each) and is read with
 // ds_read_b64_tr_b16, which hands every lane four k-values of one column: the 16 lanes of a
 // group supply the addresses of 4 k-rows x 4 column quads, and lane i receives column i of the
 // group's 16 at those four k.  Two such reads give the lane the same 8 consecutive k of its
 // column that a ds_read_b128 gives it from a k-contiguous tile, so the MFMAs and the epilogue
 // do not change.
-enum { MODE_NT = 0, MODE_NN = 1, MODE_TN = 2 };
+enum { MODE_NT = 0, MODE_NN = 1, MODE_TN = 2, MODE_TN_WIDE = 3 };
 typedef short i16x4 __attribute__((ext_vector_type(4)));
 typedef int i32x4 __attribute__((ext_vector_type(4)));
 
@@ -293,7 +295,7 @@ __device__ __forceinline__ int swz_kmajor(int kr) { return ((kr & 3) << 2) | (((
 // MFMAs and activation loads only for its rows rounded up to 64.
 template <int EPI, int XF, int MODE, bool GATHER>
 __device__ __forceinline__ void gemm_tile(const MfmaArgs& a, char* smem, int slot, int row0, int row_end, int n0) {
-  constexpr bool TA = MODE == MODE_TN, TB = MODE != MODE_NT;  // k-major left / right operand
+  constexpr bool TA = MODE == MODE_TN || MODE == MODE_TN_WIDE, TB = MODE != MODE_NT;  // k-major left / right operand
   constexpr bool kGated = EPI == EPI_SWIGLU || EPI == EPI_SWIGLU_KEEP;
   constexpr int KS = BK / 32;             // 32-wide MFMA slices per stage
   constexpr int kLoadsX = TA ? 8 : 2 * XF;  // 1-KiB wave loads per wave for the left tile (8 rows, or 2 k-rows, each)
@@ -313,16 +315,20 @@ __device__ __forceinline__ void gemm_tile(const MfmaArgs& a, char* smem, int slo
   const uint16_t* tileW;
   uint32_t a_extent, w_extent;          // bytes the two descriptors cover
   int stepA = BK * 2, stepW = BK * 2;   // bytes one K step advances in each operand
-  // MODE_TN: a slot's rows of the k-major operands may cover more than 4 GiB, so the descriptors
-  // are rebuilt for every K step (base advanced by whole steps, extent = what is left of the slot)
+  // MODE_TN, MODE_TN_WIDE: the contraction ends with the slot's last row, wherever in a K step that
+  // is, so the descriptors are rebuilt for every K step (base advanced by whole steps, extent =
+  // what is left of the slot); in 64-bit arithmetic where a slot's rows may cover more than 4 GiB
   [[maybe_unused]] unsigned long long a_bytes = 0, w_bytes = 0, stepA64 = 0, stepW64 = 0;
-  if constexpr (MODE == MODE_TN) {
+  if constexpr (TA) {
     // The descriptors start at the slot's first row and this tile's first column and end with
     // the slot's last row: the rows of the last, partial K step that belong to the next slot
     // read as zero.
     long long s0, s1;
     clip_slot(a.slot_offsets, slot, a.k_rows, &s0, &s1);
-    K = int(s1 - s0);
+    // (the offsets are int32 values read through the vector memory path: tell the compiler that they are
+    // the same in every lane, the descriptors built from them are scalar operands)
+    s0 = __builtin_amdgcn_readfirstlane((int)s0);
+    K = __builtin_amdgcn_readfirstlane(int(s1 - s0));
     const int m0 = row0 - slot * a.rows_per_slot;
     tileA = a.A + (size_t)s0 * a.lda + m0;
     tileW = a.W + (size_t)s0 * a.ldw + n0;
@@ -330,8 +336,8 @@ __device__ __forceinline__ void gemm_tile(const MfmaArgs& a, char* smem, int slo
     w_bytes = K > 0 ? ((unsigned long long)K * (unsigned)a.ldw - (unsigned)n0) * 2ull : 0ull;
     stepA64 = 64ull * (unsigned)a.lda * 2ull;
     stepW64 = 64ull * (unsigned)a.ldw * 2ull;
-    a_extent = a_bytes > 0xFFFFFFFFull ? 0xFFFFFFFFu : (uint32_t)a_bytes;  // (unused: see issue())
-    w_extent = w_bytes > 0xFFFFFFFFull ? 0xFFFFFFFFu : (uint32_t)w_bytes;
+    a_extent = (uint32_t)a_bytes;  // MODE_TN: the host checked that they fit; MODE_TN_WIDE: unused, see issue()
+    w_extent = (uint32_t)w_bytes;
     stepA = 0;
     stepW = 0;
   } else if constexpr (MODE == MODE_NN) {
@@ -351,9 +357,6 @@ __device__ __forceinline__ void gemm_tile(const MfmaArgs& a, char* smem, int slo
     tileW = a.W + (size_t)slot * a.w_rows * K;
     w_extent = (uint32_t)((unsigned long long)a.w_rows * K * 2);
   }
-  const __amdgpu_buffer_rsrc_t rsrcA = __builtin_amdgcn_make_buffer_rsrc((void*)tileA, 0, (int)a_extent, 0x00020000);
-  const __amdgpu_buffer_rsrc_t rsrcB = __builtin_amdgcn_make_buffer_rsrc((void*)tileW, 0, (int)w_extent, 0x00020000);
-  const __amdgpu_buffer_rsrc_t rsrcNull = __builtin_amdgcn_make_buffer_rsrc((void*)a.A, 0, 0, 0x00020000);
   const i32x4 wordsA = rsrc_words(tileA, a_extent), wordsB = rsrc_words(tileW, w_extent);
   const i32x4 wordsNull = rsrc_words(a.A, 0);
   const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)smem;
@@ -494,44 +497,32 @@ __device__ __forceinline__ void gemm_tile(const MfmaArgs& a, char* smem, int slo
                    const bf16x8* mw = nullptr, const bf16x8* mx = nullptr) {
     // a step past the end of K is "loaded" through a zero-length descriptor: no memory traffic
     const bool real_a = a_step < k_steps, real_w = w_step < k_steps;
-    char* sX = smem + a_stage_off(a_stage);
-    char* sW = smem + w_stage_off(w_stage);
-    if constexpr (MODE != MODE_NT) {
-      i32x4 wa = real_a ? wordsA : wordsNull, wb = real_w ? wordsB : wordsNull;
-      if constexpr (MODE == MODE_TN) {
-        const unsigned long long offA = (unsigned long long)(unsigned)a_step * stepA64;
-        const unsigned long long offW = (unsigned long long)(unsigned)w_step * stepW64;
-        const unsigned long long leftA = a_bytes > offA ? a_bytes - offA : 0ull;
-        const unsigned long long leftW = w_bytes > offW ? w_bytes - offW : 0ull;
-        wa = rsrc_words((const char*)tileA + offA, leftA > 0xFFFFFFFFull ? 0xFFFFFFFFu : (uint32_t)leftA);
-        wb = rsrc_words((const char*)tileW + offW, leftW > 0xFFFFFFFFull ? 0xFFFFFFFFu : (uint32_t)leftW);
-      }
-      const uint32_t ldsX = lds0 + a_stage_off(a_stage), ldsW = lds0 + w_stage_off(w_stage);
-#pragma unroll
-      for (int q = q0; q < q1; ++q) {
-        const bool isx = q < kLoadsX;
-        const i32x4 words = isx ? wa : wb;
-        const uint32_t lds = isx ? ldsX + (wave * kLoadsX + q) * 1024 : ldsW + (wave * kLoadsW + q - kLoadsX) * 1024;
-        const int voff = isx ? voffX[q < kLoadsX ? q : 0] : voffW[q >= kLoadsX ? q - kLoadsX : 0];
-        const int soff = isx ? a_step * stepA : w_step * stepW;
-        if (with_mfma != nullptr && q == q0) mfma_then_load16_to_lds(*with_mfma, *mw, *mx, words, lds, voff, soff);
-        else load16_to_lds(words, lds, voff, soff);
-      }
-      return;
+    i32x4 wa = real_a ? wordsA : wordsNull, wb = real_w ? wordsB : wordsNull;
+    if constexpr (MODE == MODE_TN) {
+      const uint32_t offA = (uint32_t)a_step * (uint32_t)stepA64, offW = (uint32_t)w_step * (uint32_t)stepW64;
+      // bytes left of the slot: a step that begins inside the slot begins inside both extents (the
+      // tile's first column lies inside the operand's row)
+      const uint32_t leftA = real_a ? a_extent - offA : 0u, leftW = real_w ? w_extent - offW : 0u;
+      wa = rsrc_words((const char*)tileA + offA, leftA);
+      wb = rsrc_words((const char*)tileW + offW, leftW);
+    } else if constexpr (MODE == MODE_TN_WIDE) {
+      const unsigned long long offA = (unsigned long long)(unsigned)a_step * stepA64;
+      const unsigned long long offW = (unsigned long long)(unsigned)w_step * stepW64;
+      const unsigned long long leftA = a_bytes > offA ? a_bytes - offA : 0ull;
+      const unsigned long long leftW = w_bytes > offW ? w_bytes - offW : 0ull;
+      wa = rsrc_words((const char*)tileA + offA, leftA > 0xFFFFFFFFull ? 0xFFFFFFFFu : (uint32_t)leftA);
+      wb = rsrc_words((const char*)tileW + offW, leftW > 0xFFFFFFFFull ? 0xFFFFFFFFu : (uint32_t)leftW);
     }
-    const __amdgpu_buffer_rsrc_t ra = real_a ? rsrcA : rsrcNull;
-    const __amdgpu_buffer_rsrc_t rb = real_w ? rsrcB : rsrcNull;
+    const uint32_t ldsX = lds0 + a_stage_off(a_stage), ldsW = lds0 + w_stage_off(w_stage);
 #pragma unroll
     for (int q = q0; q < q1; ++q) {
-      if (q < kLoadsX) {
-        const int u = wave * kLoadsX + q;
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(ra, (__attribute__((address_space(3))) void*)(sX + u * 1024), 16,
-                                                 voffX[q], a_step * stepA, 0, 0);
-      } else {
-        const int u = wave * kLoadsW + (q - kLoadsX);
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(rb, (__attribute__((address_space(3))) void*)(sW + u * 1024), 16,
-                                                 voffW[q - kLoadsX], w_step * stepW, 0, 0);
-      }
+      const bool isx = q < kLoadsX;
+      const i32x4 words = isx ? wa : wb;
+      const uint32_t lds = isx ? ldsX + (wave * kLoadsX + q) * 1024 : ldsW + (wave * kLoadsW + q - kLoadsX) * 1024;
+      const int voff = isx ? voffX[q < kLoadsX ? q : 0] : voffW[q >= kLoadsX ? q - kLoadsX : 0];
+      const int soff = isx ? a_step * stepA : w_step * stepW;
+      if (with_mfma != nullptr && q == q0) mfma_then_load16_to_lds(*with_mfma, *mw, *mx, words, lds, voff, soff);
+      else load16_to_lds(words, lds, voff, soff);
     }
   };
   // A stage is consumed as four units: 32-wide slice s (0, 1) x half hw (0, 1) of the wave's weight
@@ -583,7 +574,7 @@ __device__ __forceinline__ void gemm_tile(const MfmaArgs& a, char* smem, int slo
     for (int m = 0; m < kMfmas; ++m) {
       if (m < NR) read_r(m, w_stage, ns, nhw, nws, x_stage, xs, nxset, j0, j1, x_first);
       const int l0 = q0 + (NL * m) / kMfmas, l1 = q0 + (NL * (m + 1)) / kMfmas;
-      if (MODE != MODE_NT && l1 > l0) {
+      if (l1 > l0) {
         issue(ld_a_stage, ld_a_step, ld_w_stage, ld_w_step, l0, l1, &acc[4 * hw + m / NA][m % NA], &wf[ws][m / NA],
               &xf[xset][m % NA]);
       } else {
