@@ -144,6 +144,16 @@ def test_ffn_forward_train_and_backward_ragged(act, d, ffn):
     _ffn_backward_case(cfg, [257, 0, 1, 512, 300, 255, 74, 1], 3)
 
 
+def test_weight_gradients_over_every_k_step_count_of_the_unrolled_loop():
+    """The K loop is unrolled six times with a remainder chain, and three weight stages are in flight
+    when it ends: slots of 1 ... 13 K steps (whole and partial) reach every exit of that chain in
+    the weight-gradient kernels, whose contraction length is the slot's row count."""
+    counts = [64, 100, 192, 250, 300, 384, 420, 500, 576, 630, 690, 768, 800]
+    assert [(c + 63) // 64 for c in counts] == list(range(1, 14))
+    cfg = scaled(CONFIGS["c1_tiny"], act="swiglu", dtype="bf16", T=sum(counts) // 2, k=2, d=256, ffn=128, N=13, c=1)
+    _ffn_backward_case(cfg, counts, 17)
+
+
 def test_ffn_backward_many_slots_mostly_empty():
     cfg = scaled(CONFIGS["c1_tiny"], act="swiglu", dtype="bf16", T=600, k=2, d=256, ffn=128, N=4, c=5)
     counts = [0] * 20
